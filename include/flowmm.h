@@ -1,0 +1,114 @@
+/*
+ * flowmm.h - C ABI of the MI355X (gfx950) FlowMM prefill-time KV-cache merge.
+ *
+ * The library compresses the KV cache of a multimodal prompt right after prefill,
+ * following FlowMM (arXiv 2511.05534), Method section:
+ *   - flowmm_plan : scores every cached key with the attention of the last W prompt
+ *     tokens (the proxy tokens; "Information Flow Guided Merging", importance equation),
+ *     measures the layer's cross-modal interaction ratio rho and compares it with theta
+ *     (same section, rho equation and threshold rule), picks the top-B pivots per KV head,
+ *     and matches every non-pivot key to its most cosine-similar pivot whose importance
+ *     does not exceed tau ("Sensitivity-Adaptive Token Matching", both equations); in an
+ *     intra-modal layer (rho <= theta) only pivots of the token's own modality qualify.
+ *   - flowmm_merge: folds every matched non-pivot K/V row into its pivot by a uniform mean
+ *     (the paper's generic K_merged = f_merge(K, S), Preliminary) and writes a compacted cache.
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library allocates no
+ *     device memory, never synchronises and launches only on the stream it is given.
+ *   - Arrays inside flowmm_params are HOST pointers, read during the call only.
+ *   - Tokens of a batch are packed: sequence b owns tokens [cu_seqlens[b], cu_seqlens[b+1]).
+ *     "T" below is cu_seqlens[batch]; "SB" is the sum of budget_tokens.
+ *   - K and V: element (layer l, kv head g, packed token t, channel c) lives at
+ *     base + l*stride_layer + g*stride_head + t*stride_token + c   (elements, c contiguous).
+ *     Q holds only the window rows: token index b*W + r is row r (prompt position L_b-W+r) of
+ *     sequence b; heads are query heads; query head h reads KV head h / (Hq/Hkv).
+ *   - Device pointers must be 16-byte aligned, strides multiples of 16 bytes.
+ *   - Errors in the arguments are found on the host before anything is launched; the call
+ *     then returns a code and flowmm_last_error() describes it.  Nothing was enqueued.
+ */
+#ifndef FLOWMM_H
+#define FLOWMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FLOWMM_OK = 0,
+  FLOWMM_EINVAL = 1,       /* malformed argument (message says which) */
+  FLOWMM_EUNSUPPORTED = 2, /* valid but not built: head_dim other than 64/128, ... */
+  FLOWMM_EWORKSPACE = 3,   /* workspace_bytes smaller than flowmm_plan_sizes reports */
+  FLOWMM_EHIP = 4          /* a HIP call failed (launch error, no device) */
+} flowmm_status;
+
+typedef enum { FLOWMM_F32 = 0, FLOWMM_BF16 = 1 } flowmm_dtype;
+
+enum { FLOWMM_TEXT = 0, FLOWMM_IMAGE = 1 };
+enum { FLOWMM_MODE_INTRA = 0, FLOWMM_MODE_CROSS = 1 };
+
+/* Half-open token range [begin, end) local to its sequence, with its modality. */
+typedef struct {
+  int32_t begin, end, modality;
+} flowmm_span;
+
+typedef struct {
+  int32_t n_layers, n_q_heads, n_kv_heads; /* n_q_heads % n_kv_heads == 0 */
+  int32_t head_dim;                        /* 64 or 128 */
+  int32_t dtype;                           /* flowmm_dtype of K, V, Q and of the outputs */
+  int32_t batch;                           /* >= 1 */
+  const int32_t *cu_seqlens;               /* host [batch+1], cu_seqlens[0] == 0, increasing */
+  const int32_t *budget_tokens;            /* host [batch], W <= B_b <= L_b (tokens kept per KV head) */
+  const flowmm_span *spans;                /* host, all sequences back to back */
+  const int32_t *cu_spans;                 /* host [batch+1]; spans of b sorted, contiguous, covering [0,L_b) */
+  int32_t window;                          /* W >= 1, W <= every L_b */
+  float scale;                             /* logit scale; 0 means 1/sqrt(head_dim) */
+  float theta;                             /* cross-modal merging iff rho > theta */
+  const float *tau;                        /* host [batch]; pivot j is sensitive iff I_j > tau_b;
+                                              +inf disables the gate, a negative value drops everything */
+  int64_t k_stride_layer, k_stride_head, k_stride_token; /* elements; the same strides address V */
+  int64_t q_stride_layer, q_stride_head, q_stride_token;
+} flowmm_params;
+
+/* The plan: device buffers the caller allocates; flowmm_plan fills them, flowmm_merge reads
+ * kept_idx and assign.  Sizes in bytes come from flowmm_plan_sizes, in this field order. */
+typedef struct {
+  float *importance;  /* [Lyr][Hkv][T]  proxy importance, normalised so each sequence sums to 1 */
+  float *rho;         /* [Lyr][batch]   cross-modal interaction ratio */
+  int32_t *mode;      /* [Lyr][batch]   FLOWMM_MODE_CROSS iff rho > theta */
+  int32_t *kept_idx;  /* [Lyr][Hkv][SB] positions (local to the sequence) of the pivots, ascending;
+                                        the pivots of sequence b start at sum_{b'<b} B_b' ("slot" = index there) */
+  int32_t *assign;    /* [Lyr][Hkv][T]  pivot: its own slot; other tokens: matched slot, or -1 if no
+                                        pivot is eligible (the token is then simply evicted) */
+  int32_t *n_dropped; /* [Lyr][Hkv][batch] number of -1 entries */
+} flowmm_plan_buffers;
+
+/* Bytes of each plan buffer (6 values, field order above) and of the scratch workspace that
+ * flowmm_plan / flowmm_merge need for these shapes.  Pure host computation. */
+flowmm_status flowmm_plan_sizes(const flowmm_params *p, size_t plan_bytes[6], size_t *workspace_bytes);
+
+/* Score, flow, select and match for all layers, heads and sequences.  K [Lyr][Hkv][T][d] and
+ * Q_window [Lyr][Hq][batch*W][d] are read through the strides in p.  workspace: device scratch,
+ * contents undefined afterwards.  stream: a hipStream_t (NULL = default stream). */
+flowmm_status flowmm_plan(const flowmm_params *p, const void *K, const void *Q_window,
+                          const flowmm_plan_buffers *plan, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/* K_out, V_out [Lyr][Hkv][SB][d] contiguous, dtype of the inputs:
+ *   out[slot] = (row[kept_idx[slot]] + sum of rows assigned to slot) / (1 + their number),
+ * accumulated in fp32 in ascending token order and rounded to nearest-even; a pivot nobody
+ * merges into is copied bit for bit.  Outputs must not overlap K or V. */
+flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *plan, const void *K,
+                           const void *V, void *K_out, void *V_out, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* Message of the last failing call on this thread (static storage, never NULL). */
+const char *flowmm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLOWMM_H */

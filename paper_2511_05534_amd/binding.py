@@ -1,0 +1,184 @@
+"""Thin ctypes binding of libflowmm.so (include/flowmm.h): argument marshalling only.
+
+Every step of the method runs in the library's HIP kernels; if the library is missing this
+module raises instead of falling back to anything.  PyTorch appears only as the owner of
+device memory and streams (`data_ptr()`, `cuda_stream`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+FLOWMM_OK, FLOWMM_EINVAL, FLOWMM_EUNSUPPORTED, FLOWMM_EWORKSPACE, FLOWMM_EHIP = range(5)
+FLOWMM_F32, FLOWMM_BF16 = 0, 1
+STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
+PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
+EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_last_error")
+
+
+class flowmm_span(C.Structure):
+    _fields_ = [("begin", C.c_int32), ("end", C.c_int32), ("modality", C.c_int32)]
+
+
+class flowmm_params(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("dtype", C.c_int32), ("batch", C.c_int32),
+        ("cu_seqlens", C.POINTER(C.c_int32)), ("budget_tokens", C.POINTER(C.c_int32)),
+        ("spans", C.POINTER(flowmm_span)), ("cu_spans", C.POINTER(C.c_int32)),
+        ("window", C.c_int32), ("scale", C.c_float), ("theta", C.c_float),
+        ("tau", C.POINTER(C.c_float)),
+        ("k_stride_layer", C.c_int64), ("k_stride_head", C.c_int64), ("k_stride_token", C.c_int64),
+        ("q_stride_layer", C.c_int64), ("q_stride_head", C.c_int64), ("q_stride_token", C.c_int64),
+    ]
+
+
+class flowmm_plan_buffers(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in PLAN_FIELDS]
+
+
+class FlowMMError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 5 else status}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def load(build_if_missing: bool = True):
+    """Load libflowmm.so; it is built first only if no library is there at all."""
+    global _lib
+    if _lib is None:
+        path = _build.library_path()
+        if not os.path.exists(path):
+            if not build_if_missing:
+                raise FileNotFoundError(path)
+            _build.build_library()
+        lib = C.CDLL(path)
+        lib.flowmm_last_error.restype = C.c_char_p
+        lib.flowmm_plan_sizes.argtypes = [C.POINTER(flowmm_params), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        lib.flowmm_plan.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p,
+                                    C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.flowmm_merge.argtypes = [C.POINTER(flowmm_params), C.POINTER(flowmm_plan_buffers), C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge):
+            f.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _check(status: int):
+    if status != FLOWMM_OK:
+        raise FlowMMError(status, load().flowmm_last_error().decode())
+
+
+class Params:
+    """Owns the host arrays a flowmm_params points to."""
+
+    def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: str,
+                 seqlens: Sequence[int], budgets: Sequence[int],
+                 spans: Sequence[Sequence[Tuple[int, int, int]]], window: int, theta: float,
+                 tau: Sequence[float], scale: float = 0.0,
+                 k_strides: Tuple[int, int, int] | None = None,
+                 q_strides: Tuple[int, int, int] | None = None):
+        self.batch = len(seqlens)
+        self.seqlens = [int(x) for x in seqlens]
+        self.budgets = [int(x) for x in budgets]
+        self.total_tokens = int(sum(self.seqlens))
+        self.sum_budget = int(sum(self.budgets))
+        self.dtype = dtype
+        self._cu = np.concatenate([[0], np.cumsum(self.seqlens)]).astype(np.int32)
+        self._bud = np.asarray(self.budgets, dtype=np.int32)
+        flat = [s for seq in spans for s in seq]
+        self._spans = (flowmm_span * max(1, len(flat)))(*[flowmm_span(int(a), int(b), int(m)) for a, b, m in flat])
+        self._cu_spans = np.concatenate([[0], np.cumsum([len(s) for s in spans])]).astype(np.int32)
+        self._tau = np.asarray(tau, dtype=np.float32)
+        T, W, d = self.total_tokens, int(window), int(head_dim)
+        if k_strides is None:
+            k_strides = (n_kv_heads * T * d, T * d, d)
+        if q_strides is None:
+            q_strides = (n_q_heads * self.batch * W * d, self.batch * W * d, d)
+        self.c = flowmm_params(
+            n_layers, n_q_heads, n_kv_heads, head_dim, FLOWMM_BF16 if dtype == "bf16" else FLOWMM_F32,
+            self.batch, self._cu.ctypes.data_as(C.POINTER(C.c_int32)),
+            self._bud.ctypes.data_as(C.POINTER(C.c_int32)), self._spans,
+            self._cu_spans.ctypes.data_as(C.POINTER(C.c_int32)), W, float(scale), float(theta),
+            self._tau.ctypes.data_as(C.POINTER(C.c_float)), *k_strides, *q_strides)
+        self.n_layers, self.n_q_heads, self.n_kv_heads, self.head_dim, self.window = \
+            n_layers, n_q_heads, n_kv_heads, head_dim, W
+
+    @classmethod
+    def from_workload(cls, wl, theta: float | None = None, tau: Sequence[float] | None = None):
+        return cls(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.seqlens, wl.budgets,
+                   wl.spans, wl.window, wl.theta if theta is None else theta, wl.tau if tau is None else tau)
+
+
+def flowmm_plan_sizes(params: Params):
+    sizes = (C.c_size_t * 6)()
+    ws = C.c_size_t(0)
+    _check(load().flowmm_plan_sizes(C.byref(params.c), sizes, C.byref(ws)))
+    return [int(x) for x in sizes], int(ws.value)
+
+
+def _plan_struct(plan_ptrs: Sequence[int]) -> flowmm_plan_buffers:
+    return flowmm_plan_buffers(*[C.c_void_p(int(p)) for p in plan_ptrs])
+
+
+def flowmm_plan(params: Params, K: int, Q_window: int, plan_ptrs: Sequence[int], workspace: int,
+                workspace_bytes: int, stream: int = 0):
+    """All arguments after `params` are raw device addresses (ints)."""
+    pb = _plan_struct(plan_ptrs)
+    _check(load().flowmm_plan(C.byref(params.c), C.c_void_p(K), C.c_void_p(Q_window), C.byref(pb),
+                              C.c_void_p(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+
+def flowmm_merge(params: Params, plan_ptrs: Sequence[int], K: int, V: int, K_out: int, V_out: int,
+                 workspace: int, workspace_bytes: int, stream: int = 0):
+    pb = _plan_struct(plan_ptrs)
+    _check(load().flowmm_merge(C.byref(params.c), C.byref(pb), C.c_void_p(K), C.c_void_p(V),
+                               C.c_void_p(K_out), C.c_void_p(V_out), C.c_void_p(workspace),
+                               C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+
+# ---- device-memory plumbing (PyTorch owns the memory; nothing below computes) ------------------
+class DeviceBuffers:
+    """Plan buffers, outputs and workspace for one Params, allocated with torch on `device`."""
+
+    def __init__(self, params: Params, device="cuda:0"):
+        import torch
+        self.params = params
+        sizes, ws = flowmm_plan_sizes(params)
+        Lyr, Hkv, T, SB, Bt = params.n_layers, params.n_kv_heads, params.total_tokens, params.sum_budget, params.batch
+        tdt = torch.bfloat16 if params.dtype == "bf16" else torch.float32
+        self.importance = torch.empty((Lyr, Hkv, T), dtype=torch.float32, device=device)
+        self.rho = torch.empty((Lyr, Bt), dtype=torch.float32, device=device)
+        self.mode = torch.empty((Lyr, Bt), dtype=torch.int32, device=device)
+        self.kept_idx = torch.empty((Lyr, Hkv, SB), dtype=torch.int32, device=device)
+        self.assign = torch.empty((Lyr, Hkv, T), dtype=torch.int32, device=device)
+        self.n_dropped = torch.empty((Lyr, Hkv, Bt), dtype=torch.int32, device=device)
+        for name, nbytes in zip(PLAN_FIELDS, sizes):
+            t = getattr(self, name)
+            assert t.numel() * t.element_size() == nbytes, (name, nbytes)
+        self.K_out = torch.empty((Lyr, Hkv, SB, params.head_dim), dtype=tdt, device=device)
+        self.V_out = torch.empty_like(self.K_out)
+        self.workspace_bytes = ws
+        self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=device)
+
+    @property
+    def plan_ptrs(self) -> List[int]:
+        return [getattr(self, n).data_ptr() for n in PLAN_FIELDS]
+
+    def plan(self, K, Q, stream: int = 0):
+        flowmm_plan(self.params, K.data_ptr(), Q.data_ptr(), self.plan_ptrs, self.workspace.data_ptr(),
+                    self.workspace_bytes, stream)
+
+    def merge(self, K, V, stream: int = 0):
+        flowmm_merge(self.params, self.plan_ptrs, K.data_ptr(), V.data_ptr(), self.K_out.data_ptr(),
+                     self.V_out.data_ptr(), self.workspace.data_ptr(), self.workspace_bytes, stream)

@@ -1,0 +1,141 @@
+// Device-side helpers shared by the gfx950 kernels: MFMA fragments read straight from global
+// memory or LDS in 16-byte chunks, wave64 reductions, and metadata look-ups.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "layout.h"
+
+namespace flowmm {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+// A row of head_dim elements is NCH 16-byte chunks.  In every contraction lane (n, half) of a
+// wave (n = lane & 31, half = lane >> 5) owns the chunks 2t+half, t = 0..NF-1, of row n of
+// its operand tile, so both operands of an MFMA see the same channel in the same k slot.
+template <bool BF16, int D>
+struct Cfg {
+  static constexpr int kElemBytes = BF16 ? 2 : 4;
+  static constexpr int NCH = D * kElemBytes / 16;  // chunks per row
+  static constexpr int NF = NCH / 2;               // fragments per lane per row
+  static constexpr int kElemsPerChunk = 16 / kElemBytes;
+};
+
+// acc[m][n] += sum over the chunk's channels of a(row m) * b(row n); 32x32 tile, lane holds
+// column n = lane & 31 and rows m = 8*(i/4) + 4*(lane>>5) + (i%4), i = 0..15.
+template <bool BF16>
+__device__ __forceinline__ void mma_chunk(f32x16_t &acc, const uint4 &a, const uint4 &b) {
+  if constexpr (BF16) {
+    bf16x8_t av, bv;
+    __builtin_memcpy(&av, &a, 16);
+    __builtin_memcpy(&bv, &b, 16);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+  } else {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ int acc_row(int i, int half) { return 8 * (i >> 2) + 4 * half + (i & 3); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round-to-nearest-even float -> bf16 bits (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+template <bool BF16>
+__device__ __forceinline__ void chunk_to_floats(const uint4 &c, float *f) {
+  if constexpr (BF16) {
+    f[0] = bf16_bits_to_float(c.x & 0xffffu); f[1] = bf16_bits_to_float(c.x >> 16);
+    f[2] = bf16_bits_to_float(c.y & 0xffffu); f[3] = bf16_bits_to_float(c.y >> 16);
+    f[4] = bf16_bits_to_float(c.z & 0xffffu); f[5] = bf16_bits_to_float(c.z >> 16);
+    f[6] = bf16_bits_to_float(c.w & 0xffffu); f[7] = bf16_bits_to_float(c.w >> 16);
+  } else {
+    f[0] = __uint_as_float(c.x); f[1] = __uint_as_float(c.y);
+    f[2] = __uint_as_float(c.z); f[3] = __uint_as_float(c.w);
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ uint4 floats_to_chunk(const float *f) {
+  uint4 c;
+  if constexpr (BF16) {
+    c.x = float_to_bf16_bits(f[0]) | (float_to_bf16_bits(f[1]) << 16);
+    c.y = float_to_bf16_bits(f[2]) | (float_to_bf16_bits(f[3]) << 16);
+    c.z = float_to_bf16_bits(f[4]) | (float_to_bf16_bits(f[5]) << 16);
+    c.w = float_to_bf16_bits(f[6]) | (float_to_bf16_bits(f[7]) << 16);
+  } else {
+    c.x = __float_as_uint(f[0]); c.y = __float_as_uint(f[1]);
+    c.z = __float_as_uint(f[2]); c.w = __float_as_uint(f[3]);
+  }
+  return c;
+}
+
+template <bool BF16>
+__device__ __forceinline__ float chunk_sumsq(const uint4 &c) {
+  float f[8];
+  chunk_to_floats<BF16>(c, f);
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < (BF16 ? 8 : 4); ++j) s = fmaf(f[j], f[j], s);
+  return s;
+}
+
+// running (max, sum of exp2) pairs of a softmax row, in the log2 domain
+__device__ __forceinline__ void stat_combine(float &m, float &z, float m2, float z2) {
+  const float M = fmaxf(m, m2);
+  if (M == -INFINITY) { m = M; z = 0.f; return; }
+  z = z * fast_exp2(m - M) + z2 * fast_exp2(m2 - M);
+  m = M;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum_int(int v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// sequence that owns flat index x given an increasing cumulative table cu[0..batch]
+__device__ __forceinline__ int find_seq(const int *__restrict__ cu, int batch, int x) {
+  int lo = 0, hi = batch;  // invariant: cu[lo] <= x < cu[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= x) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+struct SeqInfo {
+  int tok_off, L, B, kept_off, win_has_img;
+  float tau;
+};
+
+__device__ __forceinline__ SeqInfo load_seq(const int *__restrict__ meta, int b) {
+  const int *r = meta + meta[MW_OFF_SEQ] + b * SW_WORDS;
+  SeqInfo s;
+  s.tok_off = r[SW_TOK_OFF];
+  s.L = r[SW_L];
+  s.B = r[SW_B];
+  s.kept_off = r[SW_KEPT_OFF];
+  s.tau = __int_as_float(r[SW_TAU]);
+  s.win_has_img = r[SW_WIN_HAS_IMG];
+  return s;
+}
+
+}  // namespace flowmm

@@ -1,0 +1,300 @@
+// C ABI of the library (include/flowmm.h): host-side argument checking, workspace layout and
+// kernel sequencing.  All arithmetic of the method runs in the kernels this file launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "../../include/flowmm.h"
+#include "kernels.h"
+
+namespace {
+
+using namespace flowmm;
+
+thread_local char g_err[512] = "";
+
+flowmm_status fail(flowmm_status code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+  Shape sh;
+  Regions rg;
+  std::vector<int32_t> words;
+  size_t plan_bytes[6];
+  size_t workspace_bytes;
+  size_t kv_extent_bytes, q_extent_bytes;
+};
+
+constexpr size_t kLdsLimit = 160 * 1024;
+
+flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
+  if (!p) return fail(FLOWMM_EINVAL, "params is NULL");
+  if (p->n_layers < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1)
+    return fail(FLOWMM_EINVAL, "n_layers, n_q_heads and n_kv_heads must be >= 1");
+  if (p->n_q_heads % p->n_kv_heads != 0)
+    return fail(FLOWMM_EINVAL, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", p->n_q_heads, p->n_kv_heads);
+  if (p->dtype != FLOWMM_F32 && p->dtype != FLOWMM_BF16) return fail(FLOWMM_EINVAL, "dtype must be FLOWMM_F32 or FLOWMM_BF16");
+  if (p->head_dim < 1) return fail(FLOWMM_EINVAL, "head_dim must be positive");
+  if (p->head_dim != 64 && p->head_dim != 128)
+    return fail(FLOWMM_EUNSUPPORTED, "head_dim %d is not built (64 and 128 are)", p->head_dim);
+  if (p->batch < 1) return fail(FLOWMM_EINVAL, "batch must be >= 1");
+  if (!p->cu_seqlens || !p->budget_tokens || !p->spans || !p->cu_spans || !p->tau)
+    return fail(FLOWMM_EINVAL, "cu_seqlens, budget_tokens, spans, cu_spans and tau must not be NULL");
+  if (p->window < 1) return fail(FLOWMM_EINVAL, "window must be >= 1");
+  if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return fail(FLOWMM_EINVAL, "scale must be finite and >= 0");
+  if (std::isnan(p->theta)) return fail(FLOWMM_EINVAL, "theta is NaN");
+  if (p->cu_seqlens[0] != 0 || p->cu_spans[0] != 0) return fail(FLOWMM_EINVAL, "cu_seqlens[0] and cu_spans[0] must be 0");
+
+  const int es = p->dtype == FLOWMM_BF16 ? 2 : 4;
+  const int epc = 16 / es;  // elements per 16-byte chunk
+  const int64_t strides[6] = {p->k_stride_layer, p->k_stride_head, p->k_stride_token,
+                              p->q_stride_layer, p->q_stride_head, p->q_stride_token};
+  for (int i = 0; i < 6; ++i)
+    if (strides[i] < 0 || strides[i] % epc != 0)
+      return fail(FLOWMM_EINVAL, "strides must be non-negative multiples of 16 bytes (%d elements)", epc);
+  if (p->k_stride_token < p->head_dim || p->q_stride_token < p->head_dim)
+    return fail(FLOWMM_EINVAL, "token strides must be at least head_dim");
+
+  Shape &sh = lo.sh;
+  sh.n_layers = p->n_layers; sh.Hq = p->n_q_heads; sh.Hkv = p->n_kv_heads; sh.G = sh.Hq / sh.Hkv;
+  sh.d = p->head_dim; sh.bf16 = p->dtype == FLOWMM_BF16; sh.batch = p->batch; sh.W = p->window;
+  sh.W_pad = (sh.W + 31) / 32 * 32;
+  sh.R_pad = sh.G * sh.W_pad;
+  const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->head_dim);
+  sh.scale_log2e = scale * 1.4426950408889634f;
+  sh.theta = p->theta;
+  sh.ks_layer = p->k_stride_layer / epc; sh.ks_head = p->k_stride_head / epc; sh.ks_tok = p->k_stride_token / epc;
+  sh.qs_layer = p->q_stride_layer / epc; sh.qs_head = p->q_stride_head / epc; sh.qs_tok = p->q_stride_token / epc;
+
+  const int batch = p->batch;
+  std::vector<int32_t> cu_score(batch + 1, 0), cu_match(batch + 1, 0), cu_task(batch + 1, 0),
+      cu_multi(batch + 1, 0), cu_part(batch + 1, 0);
+  std::vector<int32_t> seq((size_t)batch * SW_WORDS, 0);
+  int64_t sumB = 0;
+  int maxB = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t L64 = (int64_t)p->cu_seqlens[b + 1] - p->cu_seqlens[b];
+    if (L64 < 1) return fail(FLOWMM_EINVAL, "cu_seqlens must be strictly increasing (sequence %d)", b);
+    const int L = (int)L64, B = p->budget_tokens[b];
+    if (p->window > L) return fail(FLOWMM_EINVAL, "window %d exceeds the length %d of sequence %d", p->window, L, b);
+    if (B < p->window || B > L)
+      return fail(FLOWMM_EINVAL, "budget %d of sequence %d is outside [window=%d, length=%d]", B, b, p->window, L);
+    if (std::isnan(p->tau[b])) return fail(FLOWMM_EINVAL, "tau[%d] is NaN", b);
+    const int s0 = p->cu_spans[b], s1 = p->cu_spans[b + 1];
+    if (s1 <= s0) return fail(FLOWMM_EINVAL, "sequence %d has no spans", b);
+    int pos = 0, win_img = 0;
+    for (int j = s0; j < s1; ++j) {
+      const flowmm_span &sp = p->spans[j];
+      if (sp.begin != pos || sp.end <= sp.begin)
+        return fail(FLOWMM_EINVAL, "spans of sequence %d are not sorted, non-empty and contiguous (span %d)", b, j - s0);
+      if (sp.modality != FLOWMM_TEXT && sp.modality != FLOWMM_IMAGE)
+        return fail(FLOWMM_EINVAL, "span %d of sequence %d has modality %d", j - s0, b, sp.modality);
+      if (sp.modality == FLOWMM_IMAGE && sp.end > L - p->window) win_img = 1;
+      pos = sp.end;
+    }
+    if (pos != L) return fail(FLOWMM_EINVAL, "spans of sequence %d cover [0,%d), not [0,%d)", b, pos, L);
+    const int E = L - B;
+    cu_score[b + 1] = cu_score[b] + (L + kScoreTile - 1) / kScoreTile;
+    cu_match[b + 1] = cu_match[b] + (L + kMatchTile - 1) / kMatchTile;
+    cu_task[b + 1] = cu_task[b] + B + E / kTaskChunk + 1;
+    cu_multi[b + 1] = cu_multi[b] + E / (kTaskChunk + 1) + 1;
+    cu_part[b + 1] = cu_part[b] + 2 * (E / kTaskChunk) + 2;
+    int32_t *r = &seq[(size_t)b * SW_WORDS];
+    r[SW_TOK_OFF] = p->cu_seqlens[b]; r[SW_L] = L; r[SW_B] = B; r[SW_KEPT_OFF] = (int32_t)sumB;
+    std::memcpy(&r[SW_TAU], &p->tau[b], 4);
+    r[SW_SPAN_OFF] = s0; r[SW_N_SPANS] = s1 - s0; r[SW_WIN_HAS_IMG] = win_img;
+    sumB += B;
+    if (B > maxB) maxB = B;
+  }
+  const int64_t T = p->cu_seqlens[batch];
+  const int n_spans = p->cu_spans[batch];
+  const int64_t units = (int64_t)sh.n_layers * sh.Hkv;
+  if (units * T >= (int64_t)1 << 40) return fail(FLOWMM_EUNSUPPORTED, "cache too large");
+  sh.T = (int)T; sh.SB = (int)sumB; sh.maxB = maxB;
+  sh.tiles_score = cu_score[batch]; sh.tiles_match = cu_match[batch];
+  sh.tasks_total = cu_task[batch]; sh.multi_total = cu_multi[batch]; sh.part_total = cu_part[batch];
+  if (score_lds_bytes(sh) > kLdsLimit)
+    return fail(FLOWMM_EUNSUPPORTED, "(n_q_heads/n_kv_heads) x window = %d query rows per kv head do not fit in LDS", sh.R_pad);
+  if (merge_csr_lds_bytes(maxB) > kLdsLimit)
+    return fail(FLOWMM_EUNSUPPORTED, "budget %d per sequence is beyond what the merge kernel stages (32768)", maxB);
+  if ((int64_t)sh.Hq > 1024) return fail(FLOWMM_EUNSUPPORTED, "more than 1024 query heads");
+
+  // metadata words
+  std::vector<int32_t> &w = lo.words;
+  w.assign(MW_HEADER, 0);
+  auto append = [&](const std::vector<int32_t> &v) { const int off = (int)w.size(); w.insert(w.end(), v.begin(), v.end()); return off; };
+  w[MW_BATCH] = batch; w[MW_T] = sh.T; w[MW_SUMB] = sh.SB; w[MW_N_SPANS] = n_spans;
+  w[MW_OFF_SEQ] = append(seq);
+  {
+    std::vector<int32_t> sp((size_t)n_spans * 3);
+    for (int j = 0; j < n_spans; ++j) { sp[3 * j] = p->spans[j].begin; sp[3 * j + 1] = p->spans[j].end; sp[3 * j + 2] = p->spans[j].modality; }
+    const int off = append(sp);
+    w[MW_OFF_SPANS] = off;
+  }
+  w[MW_OFF_CU_SCORE] = append(cu_score);
+  w[MW_OFF_CU_MATCH] = append(cu_match);
+  w[MW_OFF_CU_TASK] = append(cu_task);
+  w[MW_OFF_CU_MULTI] = append(cu_multi);
+  w[MW_OFF_CU_PART] = append(cu_part);
+
+  // plan buffers
+  lo.plan_bytes[0] = (size_t)units * T * 4;
+  lo.plan_bytes[1] = (size_t)sh.n_layers * batch * 4;
+  lo.plan_bytes[2] = (size_t)sh.n_layers * batch * 4;
+  lo.plan_bytes[3] = (size_t)units * sumB * 4;
+  lo.plan_bytes[4] = (size_t)units * T * 4;
+  lo.plan_bytes[5] = (size_t)units * batch * 4;
+
+  // workspace regions: metadata first, then the plan and the merge scratch share the rest
+  Regions &rg = lo.rg;
+  size_t off = 0;
+  rg.meta = off; off += align256(w.size() * 4);
+  rg.mod = off; off += align256((size_t)T);
+  const size_t shared0 = off;
+  rg.part_stats = off; off += align256((size_t)units * sh.tiles_score * sh.R_pad * sizeof(float2));
+  rg.rowstat = off; off += align256((size_t)units * batch * sh.R_pad * sizeof(float2));
+  rg.cross_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.tiles_score * 4);
+  rg.plan_end = off;
+  off = shared0;
+  rg.seg_off = off; off += align256((size_t)units * (sumB + batch) * 4);
+  rg.members = off; off += align256((size_t)units * T * 4);
+  rg.tasks = off; off += align256((size_t)units * sh.tasks_total * sizeof(int4));
+  rg.n_tasks = off; off += align256((size_t)units * batch * 4);
+  rg.multi = off; off += align256((size_t)units * sh.multi_total * sizeof(int4));
+  rg.n_multi = off; off += align256((size_t)units * batch * 4);
+  rg.partials = off; off += align256((size_t)units * sh.part_total * 2 * sh.d * 4);
+  rg.merge_end = off;
+  lo.workspace_bytes = rg.plan_end > rg.merge_end ? rg.plan_end : rg.merge_end;
+
+  lo.kv_extent_bytes = ((size_t)(sh.n_layers - 1) * p->k_stride_layer + (size_t)(sh.Hkv - 1) * p->k_stride_head +
+                        (size_t)(T - 1) * p->k_stride_token + sh.d) * es;
+  lo.q_extent_bytes = ((size_t)(sh.n_layers - 1) * p->q_stride_layer + (size_t)(sh.Hq - 1) * p->q_stride_head +
+                       (size_t)((int64_t)batch * sh.W - 1) * p->q_stride_token + sh.d) * es;
+  return FLOWMM_OK;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+bool overlaps(const void *a, size_t na, const void *b, size_t nb) {
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + nb && b0 < a0 + na;
+}
+
+flowmm_status check_plan_buffers(const flowmm_plan_buffers *plan) {
+  if (!plan) return fail(FLOWMM_EINVAL, "plan is NULL");
+  const void *ptrs[6] = {plan->importance, plan->rho, plan->mode, plan->kept_idx, plan->assign, plan->n_dropped};
+  static const char *names[6] = {"importance", "rho", "mode", "kept_idx", "assign", "n_dropped"};
+  for (int i = 0; i < 6; ++i) {
+    if (!ptrs[i]) return fail(FLOWMM_EINVAL, "plan->%s is NULL", names[i]);
+    if (reinterpret_cast<uintptr_t>(ptrs[i]) & 3) return fail(FLOWMM_EINVAL, "plan->%s is not 4-byte aligned", names[i]);
+  }
+  return FLOWMM_OK;
+}
+
+void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *workspace, void *stream) {
+  std::memset(&c, 0, sizeof(c));
+  c.sh = lo.sh;
+  c.stream = reinterpret_cast<hipStream_t>(stream);
+  c.importance = plan->importance; c.rho = plan->rho; c.mode = plan->mode;
+  c.kept_idx = plan->kept_idx; c.assign = plan->assign; c.n_dropped = plan->n_dropped;
+  char *ws = reinterpret_cast<char *>(workspace);
+  c.meta = reinterpret_cast<int *>(ws + lo.rg.meta);
+  c.mod = reinterpret_cast<uint8_t *>(ws + lo.rg.mod);
+  c.part_stats = reinterpret_cast<float2 *>(ws + lo.rg.part_stats);
+  c.rowstat = reinterpret_cast<float2 *>(ws + lo.rg.rowstat);
+  c.cross_part = reinterpret_cast<float *>(ws + lo.rg.cross_part);
+  c.seg_off = reinterpret_cast<int *>(ws + lo.rg.seg_off);
+  c.members = reinterpret_cast<int *>(ws + lo.rg.members);
+  c.tasks = reinterpret_cast<int4 *>(ws + lo.rg.tasks);
+  c.n_tasks = reinterpret_cast<int *>(ws + lo.rg.n_tasks);
+  c.multi = reinterpret_cast<int4 *>(ws + lo.rg.multi);
+  c.n_multi = reinterpret_cast<int *>(ws + lo.rg.n_multi);
+  c.partials = reinterpret_cast<float *>(ws + lo.rg.partials);
+}
+
+flowmm_status hip_fail(hipError_t e, const char *what) {
+  return fail(FLOWMM_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+#define FLOWMM_API __attribute__((visibility("default")))
+
+extern "C" {
+
+FLOWMM_API const char *flowmm_last_error(void) { return g_err; }
+
+FLOWMM_API flowmm_status flowmm_plan_sizes(const flowmm_params *p, size_t plan_bytes[6], size_t *workspace_bytes) {
+  Layout lo;
+  const flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (plan_bytes) for (int i = 0; i < 6; ++i) plan_bytes[i] = lo.plan_bytes[i];
+  if (workspace_bytes) *workspace_bytes = lo.workspace_bytes;
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_plan(const flowmm_params *p, const void *K, const void *Q_window,
+                          const flowmm_plan_buffers *plan, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (!K || !Q_window || !workspace) return fail(FLOWMM_EINVAL, "K, Q_window and workspace must not be NULL");
+  if (misaligned(K) || misaligned(Q_window) || misaligned(workspace))
+    return fail(FLOWMM_EINVAL, "K, Q_window and workspace must be 16-byte aligned");
+  if ((st = check_plan_buffers(plan)) != FLOWMM_OK) return st;
+  if (workspace_bytes < lo.workspace_bytes)
+    return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
+  Ctx c;
+  fill_ctx(c, lo, plan, workspace, stream);
+  c.K = K; c.Q = Q_window;
+  hipError_t e;
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_score(c)) != hipSuccess) return hip_fail(e, "score kernels");
+  if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
+  if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *plan, const void *K,
+                           const void *V, void *K_out, void *V_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (!K || !V || !K_out || !V_out || !workspace)
+    return fail(FLOWMM_EINVAL, "K, V, K_out, V_out and workspace must not be NULL");
+  if (misaligned(K) || misaligned(V) || misaligned(K_out) || misaligned(V_out) || misaligned(workspace))
+    return fail(FLOWMM_EINVAL, "K, V, K_out, V_out and workspace must be 16-byte aligned");
+  if ((st = check_plan_buffers(plan)) != FLOWMM_OK) return st;
+  const size_t out_bytes = (size_t)lo.sh.n_layers * lo.sh.Hkv * lo.sh.SB * lo.sh.d * (lo.sh.bf16 ? 2 : 4);
+  const void *ins[2] = {K, V};
+  void *outs[2] = {K_out, V_out};
+  for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
+      if (overlaps(outs[i], out_bytes, ins[j], lo.kv_extent_bytes))
+        return fail(FLOWMM_EINVAL, "outputs must not overlap K or V (in-place compaction is not supported)");
+  if (overlaps(K_out, out_bytes, V_out, out_bytes)) return fail(FLOWMM_EINVAL, "K_out and V_out overlap");
+  if (workspace_bytes < lo.workspace_bytes)
+    return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
+  Ctx c;
+  fill_ctx(c, lo, plan, workspace, stream);
+  c.K = K; c.V = V; c.K_out = K_out; c.V_out = V_out;
+  hipError_t e;
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), false)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
+  return FLOWMM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher enqueues on ctx.stream and
+// returns the hipError_t of the launch; none of them synchronises or allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "layout.h"
+
+namespace flowmm {
+
+struct Ctx {
+  Shape sh;
+  hipStream_t stream;
+  // inputs
+  const void *K, *V, *Q;
+  // plan buffers
+  float *importance, *rho;
+  int *mode, *kept_idx, *assign, *n_dropped;
+  // outputs
+  void *K_out, *V_out;
+  // workspace regions
+  int *meta;
+  uint8_t *mod;
+  float2 *part_stats;  // [Lyr][Hkv][tiles_score][R_pad]  (max, sum exp2) of each row over a tile
+  float2 *rowstat;     // [Lyr][Hkv][batch][R_pad]        (max, 1/sum) of each row
+  float *cross_part;   // [Lyr][Hq][tiles_score]          cross-modal mass of a head over a tile
+  int *seg_off;        // [Lyr][Hkv][SB + batch]          CSR offsets of the members of each slot
+  int *members;        // [Lyr][Hkv][T]                   evicted tokens grouped by slot, ascending
+  int4 *tasks;         // [Lyr][Hkv][tasks_total]         (slot, first member, count, partial index or -1)
+  int *n_tasks;        // [Lyr][Hkv][batch]
+  int4 *multi;         // [Lyr][Hkv][multi_total]         (slot, first partial, number of partials, members)
+  int *n_multi;        // [Lyr][Hkv][batch]
+  float *partials;     // [Lyr][Hkv][part_total][2][d]    fp32 partial row sums of K and V
+};
+
+constexpr int kMetaChunkWords = 960;
+struct MetaChunk { int w[kMetaChunkWords]; };
+
+hipError_t launch_meta_upload(const Ctx &c, const int *words, int n_words, bool expand_modality);
+hipError_t launch_score(const Ctx &c);    // stats, combine, column sums
+hipError_t launch_select(const Ctx &c);   // flow + top-B split
+hipError_t launch_match(const Ctx &c);
+hipError_t launch_merge(const Ctx &c);    // CSR build, task sums, combine
+
+// static LDS needs, used by the host to reject shapes that cannot be staged
+size_t score_lds_bytes(const Shape &sh);
+size_t merge_csr_lds_bytes(int max_budget);
+
+}  // namespace flowmm

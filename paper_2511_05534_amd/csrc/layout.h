@@ -1,0 +1,65 @@
+// Host/device shared description of one flowmm call: the metadata block that the host packs
+// into 32-bit words and a small kernel places at the head of the workspace, and the byte
+// offsets of every scratch region behind it.
+#pragma once
+#include <stdint.h>
+
+namespace flowmm {
+
+// ---- metadata block (int32 words) -------------------------------------------------------
+enum MetaWord {
+  MW_BATCH = 0,
+  MW_T,            // total packed tokens
+  MW_SUMB,         // total kept tokens per (layer, kv head)
+  MW_OFF_SEQ,      // word offset of the per-sequence records
+  MW_OFF_SPANS,    // word offset of the spans (begin, end, modality), all sequences
+  MW_N_SPANS,
+  MW_OFF_CU_SCORE, // word offset of cu_tiles_score[batch+1]
+  MW_OFF_CU_MATCH, // word offset of cu_tiles_match[batch+1]
+  MW_OFF_CU_TASK,  // word offset of cu_tasks[batch+1]   (upper bounds)
+  MW_OFF_CU_MULTI, // word offset of cu_multi[batch+1]   (upper bounds)
+  MW_OFF_CU_PART,  // word offset of cu_part[batch+1]    (upper bounds)
+  MW_HEADER = 16
+};
+
+// per-sequence record
+enum SeqWord {
+  SW_TOK_OFF = 0,  // first packed token
+  SW_L,
+  SW_B,
+  SW_KEPT_OFF,     // first slot of this sequence inside [SB]
+  SW_TAU,          // float bits
+  SW_SPAN_OFF,     // first span (index into spans)
+  SW_N_SPANS,
+  SW_WIN_HAS_IMG,  // 1 if any window row is an image token
+  SW_WORDS = 8
+};
+
+// tiling constants shared by host sizing and kernels
+constexpr int kScoreKeysPerWave = 64;
+constexpr int kScoreWaves = 4;
+constexpr int kScoreTile = kScoreKeysPerWave * kScoreWaves;  // keys per workgroup
+constexpr int kMatchTokPerWave = 64;
+constexpr int kMatchWaves = 4;
+constexpr int kMatchTile = kMatchTokPerWave * kMatchWaves;   // tokens per workgroup
+constexpr int kPivotTile = 128;                              // pivots staged in LDS at a time
+constexpr int kTaskChunk = 32;                               // members summed by one wave task
+constexpr int kCsrWaves = 16;                                // waves of the CSR-building workgroup
+
+struct Shape {
+  int n_layers, Hq, Hkv, G, d, bf16;
+  int batch, T, SB, W, W_pad, R_pad, maxB;
+  int tiles_score, tiles_match, tasks_total, multi_total, part_total;
+  float scale_log2e, theta;
+  long long ks_layer, ks_head, ks_tok;  // K/V strides in 16-byte chunks
+  long long qs_layer, qs_head, qs_tok;  // Q strides in 16-byte chunks
+};
+
+// byte offsets into the workspace (all multiples of 256)
+struct Regions {
+  size_t meta, mod, part_stats, rowstat, cross_part;       // plan
+  size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials;  // merge
+  size_t plan_end, merge_end;
+};
+
+}  // namespace flowmm

@@ -1,0 +1,170 @@
+"""Stage-wise, margin-aware comparison of the HIP path with the CPU oracle.
+
+Decisions (mode, kept set, gate, argmax) must agree exactly wherever the oracle's own fp64
+margin exceeds 1e-3 relative; inside that band the GPU's choice only has to be valid.  Each
+later stage of the oracle is then re-run from the GPU's earlier decision (teacher forcing),
+so one in-band flip does not mask or fake errors downstream.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+MARGIN = 1e-3            # relative score margin below which decisions may differ
+RTOL_I = {"bf16": 2e-4, "f32": 2e-4}   # importance / rho: fp32 accumulation and exp2 of the kernel
+ATOL_OUT = {"bf16": 2e-2, "f32": 1e-5}  # merged K/V max-abs error
+
+
+def upload(wl, device="cuda:0", layers=None):
+    """K, V [Lyr][Hkv][T][d], Q [Lyr][Hq][batch*W][d] as torch tensors of the workload dtype."""
+    import torch
+    layers = range(wl.n_layers) if layers is None else layers
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    Ks, Vs, Qs = [], [], []
+    for l in layers:
+        k, v, q = wl.layer_tensors(l)
+        Ks.append(torch.from_numpy(k).to(device).to(tdt))
+        Vs.append(torch.from_numpy(v).to(device).to(tdt))
+        Qs.append(torch.from_numpy(q).to(device).to(tdt))
+    return torch.stack(Ks), torch.stack(Vs), torch.stack(Qs)
+
+
+def run_gpu(wl, theta=None, tau=None, device="cuda:0", tensors=None):
+    """Run flowmm_plan + flowmm_merge through the C ABI; returns numpy copies of everything."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    params = fb.Params.from_workload(wl, theta=theta, tau=tau)
+    K, V, Q = tensors if tensors is not None else upload(wl, device)
+    bufs = fb.DeviceBuffers(params, device)
+    stream = torch.cuda.current_stream().cuda_stream
+    bufs.plan(K, Q, stream)
+    bufs.merge(K, V, stream)
+    torch.cuda.synchronize()
+    out = {n: getattr(bufs, n).cpu().numpy() for n in fb.PLAN_FIELDS}
+    out["K_out"] = bufs.K_out.float().cpu().numpy()
+    out["V_out"] = bufs.V_out.float().cpu().numpy()
+    return out
+
+
+def bf16_ulp(x):
+    x = np.abs(np.asarray(x, dtype=np.float64))
+    e = np.floor(np.log2(np.maximum(x, 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+class Report:
+    def __init__(self):
+        self.units = 0
+        self.select_inband = 0
+        self.match_inband = 0
+        self.gate_inband = 0
+        self.max_I_rel = 0.0
+        self.max_out_abs = 0.0
+        self.ulp_excused = 0
+        self.n_evicted = 0
+
+    def __repr__(self):
+        return (f"units={self.units} evicted={self.n_evicted} select_inband={self.select_inband} "
+                f"gate_inband={self.gate_inband} match_inband={self.match_inband} "
+                f"max_I_rel={self.max_I_rel:.2e} max_out_abs={self.max_out_abs:.2e} ulp_excused={self.ulp_excused}")
+
+
+def check_layer(oracle, wl, gpu, layer, theta=None, tau=None, kv_heads=None, seqs=None, report=None,
+                tensors_np=None):
+    """Compare one layer of the GPU result with the oracle (all sequences, chosen kv heads)."""
+    rep = report or Report()
+    theta = wl.theta if theta is None else theta
+    tau = wl.tau if tau is None else tau
+    K, V, Q = tensors_np if tensors_np is not None else wl.layer_tensors(layer)
+    W, G, d = wl.window, wl.group, wl.head_dim
+    cu, cuk = wl.cu_seqlens, wl.cu_kept
+    for b in (range(wl.batch) if seqs is None else seqs):
+        L, B = wl.seqlens[b], wl.budgets[b]
+        sl = slice(int(cu[b]), int(cu[b + 1]))
+        mod = wl.modality(b)
+        Kb, Vb = K[:, sl, :], V[:, sl, :]
+        Qb = Q[:, b * W:(b + 1) * W, :]
+        I_o, cross_o = oracle.score(Kb, Qb, mod)
+        rho_o, mode_o = oracle.flow(cross_o, theta)
+        # (1) importance and rho by relative tolerance
+        I_g = gpu["importance"][layer][:, sl].astype(np.float64)
+        rel = np.abs(I_g - I_o) / np.maximum(I_o, 1e-30)
+        # importances that underflow fp32 are compared absolutely
+        ok = (rel <= RTOL_I[wl.dtype]) | (I_o < 1e-30)
+        assert ok.all(), f"importance mismatch layer {layer} seq {b}: max rel {rel[I_o >= 1e-30].max():.3e}"
+        rep.max_I_rel = max(rep.max_I_rel, float(rel[I_o >= 1e-30].max()))
+        rho_g, mode_g = float(gpu["rho"][layer][b]), int(gpu["mode"][layer][b])
+        assert abs(rho_g - rho_o) <= RTOL_I[wl.dtype] * max(rho_o, 1e-6) + 1e-7, (rho_g, rho_o)
+        if abs(rho_o - theta) > MARGIN * abs(theta):
+            assert mode_g == mode_o, f"mode differs outside the margin: rho {rho_o} theta {theta}"
+        tau_b = float(np.float32(tau[b]))
+        for g in (range(wl.n_kv_heads) if kv_heads is None else kv_heads):
+            rep.units += 1
+            kept_g = gpu["kept_idx"][layer][g][int(cuk[b]):int(cuk[b + 1])]
+            assign_g = gpu["assign"][layer][g][sl]
+            # (2) kept set
+            assert len(kept_g) == B and (np.diff(kept_g) > 0).all(), "kept_idx not ascending/unique"
+            assert kept_g.min() >= 0 and kept_g.max() < L
+            kept_set = np.zeros(L, dtype=bool)
+            kept_set[kept_g] = True
+            assert kept_set[L - W:].all(), "a proxy token was evicted"
+            kept_o = oracle.select(I_o[g], W, B)
+            kept_o_set = np.zeros(L, dtype=bool)
+            kept_o_set[kept_o] = True
+            if B > W and B < L:
+                body = np.sort(I_o[g][:L - W])[::-1]
+                i_cut = 0.5 * (body[B - W - 1] + body[B - W])
+                inband = np.abs(I_o[g] - i_cut) <= MARGIN * i_cut
+                inband[L - W:] = False
+                rep.select_inband += int(inband.sum())
+                diff = kept_set != kept_o_set
+                assert not (diff & ~inband).any(), \
+                    f"kept set differs outside the margin (layer {layer} seq {b} head {g})"
+            else:
+                assert (kept_set == kept_o_set).all()
+            assert (assign_g[kept_g] == np.arange(B)).all(), "pivot does not own its slot"
+            # (3) match, teacher-forced from the GPU's kept set and the GPU's fp32 importances
+            # (the gate I_j > tau is an fp32 comparison on both sides)
+            I_gate = gpu["importance"][layer][g][sl].astype(np.float64)
+            gate_band = np.abs(I_o[g][kept_g] - tau_b) <= MARGIN * abs(tau_b)
+            rep.gate_inband += int(gate_band.sum())
+            assert (((I_gate[kept_g] > tau_b) == (I_o[g][kept_g] > tau_b)) | gate_band).all()
+            assign_o, nd_o, ub, us = oracle.match(Kb[g], I_gate, kept_g, mod, mode_g, tau_b, with_margins=True)
+            ev = np.flatnonzero(~kept_set)
+            rep.n_evicted += len(ev)
+            assert int(gpu["n_dropped"][layer][g][b]) == nd_o == int((assign_g[ev] == -1).sum())
+            assert ((assign_g[ev] >= -1) & (assign_g[ev] < B)).all()
+            differ = ev[assign_g[ev] != assign_o[ev]]
+            if len(differ):
+                # allowed only if the oracle's own margin is within the band and the pick is valid
+                margin_ok = (ub[differ] - us[differ]) <= MARGIN * np.abs(ub[differ])
+                assert margin_ok.all(), \
+                    f"assignment differs outside the margin (layer {layer} seq {b} head {g}): {differ[~margin_ok][:5]}"
+                Kd = Kb[g].astype(np.float64)
+                for i in differ:
+                    s = int(assign_g[i])
+                    assert s >= 0
+                    j = int(kept_g[s])
+                    assert I_gate[j] <= tau_b and (mode_g == 1 or mod[j] == mod[i]), "picked an ineligible pivot"
+                    ni, nj = np.linalg.norm(Kd[i]), np.linalg.norm(Kd[j])
+                    u = float(Kd[i] @ Kd[j] / (ni * nj)) if ni > 0 and nj > 0 else 0.0
+                    assert u >= ub[i] - MARGIN * abs(ub[i]) - 1e-12
+                rep.match_inband += len(differ)
+            # (4) merge, teacher-forced from the GPU's assignment
+            ko, vo, _ = oracle.merge(Kb[g], Vb[g], kept_g, assign_g)
+            rows = slice(int(cuk[b]), int(cuk[b + 1]))
+            for name, o in (("K_out", ko), ("V_out", vo)):
+                got = gpu[name][layer][g][rows].astype(np.float64)
+                err = np.abs(got - o)
+                tol = np.full(o.shape, ATOL_OUT[wl.dtype])
+                if wl.dtype == "bf16":
+                    ulp = bf16_ulp(o)
+                    rep.ulp_excused += int(((err > tol) & (err <= ulp)).sum())
+                    tol = np.maximum(tol, ulp)
+                assert (err <= tol).all(), \
+                    f"{name} max-abs error {err.max():.3e} (layer {layer} seq {b} head {g})"
+                rep.max_out_abs = max(rep.max_out_abs, float(err.max()))
+                # a pivot nobody merged into is a bit-exact copy
+                alone = np.bincount(assign_g[assign_g >= 0], minlength=B) == 1
+                src = (Kb if name == "K_out" else Vb)[g][kept_g]
+                assert (gpu[name][layer][g][rows][alone] == src[alone]).all()
+    return rep

@@ -1,0 +1,106 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes its buffers, and rejects malformed arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2511_05534_amd import binding as fb
+from paper_2511_05534_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "flowmm.h")).read()
+    declared = set(re.findall(r"\b(flowmm_[a-z_]+)\s*\(", header))
+    assert declared == set(fb.EXPORTS)
+    lib = fb.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(fb.flowmm_span) == 12
+    assert C.sizeof(fb.flowmm_plan_buffers) == 48
+    # int32 x6, 4 pointers, int32 + 2 floats (+pad), pointer, 6 int64
+    assert C.sizeof(fb.flowmm_params) == 24 + 32 + 16 + 8 + 48
+
+
+def params_for(**kw):
+    base = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=128, dtype="bf16", seqlens=[300, 200],
+                budgets=[30, 40], spans=[[(0, 100, 0), (100, 300, 1)], [(0, 200, 0)]], window=16,
+                theta=0.25, tau=[0.1, 0.2])
+    base.update(kw)
+    return fb.Params(**base)
+
+
+def test_plan_sizes():
+    p = params_for()
+    sizes, ws = fb.flowmm_plan_sizes(p)
+    units, T, SB = 2 * 2, 500, 70
+    assert sizes == [units * T * 4, 2 * 2 * 4, 2 * 2 * 4, units * SB * 4, units * T * 4, units * 2 * 4]
+    assert ws > 0 and ws % 256 == 0
+    for i in range(5):
+        w = wl.config(i)
+        sizes, ws = fb.flowmm_plan_sizes(fb.Params.from_workload(w))
+        assert sizes[0] == w.n_layers * w.n_kv_heads * w.total_tokens * 4
+        assert ws < 1 << 30
+
+
+BAD = [
+    (dict(n_q_heads=5), fb.FLOWMM_EINVAL, "multiple"),
+    (dict(head_dim=96), fb.FLOWMM_EUNSUPPORTED, "head_dim"),
+    (dict(window=0), fb.FLOWMM_EINVAL, "window"),
+    (dict(window=201, budgets=[250, 200]), fb.FLOWMM_EINVAL, "exceeds"),
+    (dict(budgets=[8, 40]), fb.FLOWMM_EINVAL, "budget"),
+    (dict(budgets=[301, 40]), fb.FLOWMM_EINVAL, "budget"),
+    (dict(spans=[[(0, 100, 0), (101, 300, 1)], [(0, 200, 0)]]), fb.FLOWMM_EINVAL, "contiguous"),
+    (dict(spans=[[(0, 100, 0), (100, 299, 1)], [(0, 200, 0)]]), fb.FLOWMM_EINVAL, "cover"),
+    (dict(spans=[[(0, 100, 0), (100, 300, 2)], [(0, 200, 0)]]), fb.FLOWMM_EINVAL, "modality"),
+    (dict(tau=[float("nan"), 0.1]), fb.FLOWMM_EINVAL, "tau"),
+    (dict(theta=float("nan")), fb.FLOWMM_EINVAL, "theta"),
+    (dict(scale=-1.0), fb.FLOWMM_EINVAL, "scale"),
+    (dict(k_strides=(2 * 500 * 128, 500 * 128, 100)), fb.FLOWMM_EINVAL, "stride"),
+    (dict(k_strides=(2 * 500 * 128, 500 * 128, 132)), fb.FLOWMM_EINVAL, "16 bytes"),
+    (dict(n_q_heads=64, n_kv_heads=1, window=128, budgets=[130, 140]), fb.FLOWMM_EUNSUPPORTED, "LDS"),
+    (dict(seqlens=[300, 0], budgets=[30, 0]), fb.FLOWMM_EINVAL, "increasing"),
+]
+
+
+@pytest.mark.parametrize("kw,status,word", BAD)
+def test_bad_arguments_are_rejected_on_the_host(kw, status, word):
+    p = params_for(**kw)
+    with pytest.raises(fb.FlowMMError) as ei:
+        fb.flowmm_plan_sizes(p)
+    assert ei.value.status == status
+    assert word in ei.value.message, ei.value.message
+
+
+def test_pointer_checks_happen_before_any_launch():
+    """No GPU here: these calls must fail in validation and never reach a HIP call."""
+    p = params_for()
+    sizes, ws = fb.flowmm_plan_sizes(p)
+    good = 0x10000
+    plan = [good] * 6
+    cases = [
+        (lambda: fb.flowmm_plan(p, 0, good, plan, good, ws), "NULL"),
+        (lambda: fb.flowmm_plan(p, good + 8, good, plan, good, ws), "aligned"),
+        (lambda: fb.flowmm_plan(p, good, good, [good, good, 0, good, good, good], good, ws), "plan->mode"),
+        (lambda: fb.flowmm_merge(p, plan, good, good, 0, good, good, ws), "NULL"),
+        (lambda: fb.flowmm_merge(p, plan, good, 1 << 40, good + 256, 1 << 41, good, ws), "overlap"),
+        (lambda: fb.flowmm_merge(p, plan, good, 1 << 40, 1 << 41, 1 << 41, 1 << 42, ws), "overlap"),
+    ]
+    for call, word in cases:
+        with pytest.raises(fb.FlowMMError) as ei:
+            call()
+        assert ei.value.status == fb.FLOWMM_EINVAL and word in ei.value.message, ei.value.message
+    with pytest.raises(fb.FlowMMError) as ei:
+        fb.flowmm_plan(p, good, good, plan, good, ws - 1)
+    assert ei.value.status == fb.FLOWMM_EWORKSPACE
+
+
+def test_last_error_is_never_null():
+    assert isinstance(fb.load().flowmm_last_error(), bytes)

@@ -1,0 +1,159 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from paper_2511_05534_amd import workloads as wl
+
+from parity_utils import Report, check_layer, run_gpu, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def small(name, dtype="bf16", Hq=4, Hkv=2, d=128, W=32, spans=((40, 300, 60),), pct=(15,), seed=11,
+          n_layers=2, budgets=None, first_mod=wl.TEXT, theta=0.25, tau_factor=4.0):
+    return wl.make_workload(name, dtype, seed, n_layers, Hq, Hkv, d, W, [list(s) for s in spans], list(pct),
+                            theta=theta, tau_factor=tau_factor, budgets=budgets, first_mod=first_mod)
+
+
+SMALL_CASES = {
+    "mha_bf16_d128": dict(Hq=2, Hkv=2),
+    "gqa_bf16_ragged_tail": dict(Hq=6, Hkv=2, spans=((37, 411, 83),), W=32),
+    "f32_d64_w16": dict(dtype="f32", Hq=4, Hkv=4, d=64, W=16, spans=((32, 256, 32),), pct=(20,)),
+    "f32_d128": dict(dtype="f32", Hq=2, Hkv=1, d=128, W=8, spans=((20, 200, 19),)),
+    "bf16_d64_gqa": dict(Hq=8, Hkv=2, d=64, W=24, spans=((50, 500, 77),)),
+    "window_5": dict(Hq=3, Hkv=3, W=5, spans=((16, 180, 33),)),
+    "window_40_pads_to_64": dict(Hq=4, Hkv=2, W=40, spans=((30, 520, 90),)),
+    "image_tokens_in_window": dict(Hq=4, Hkv=2, W=32, spans=((30, 400, 10, 12),), pct=(12,)),
+    "image_first": dict(Hq=2, Hkv=2, W=16, spans=((200, 100),), first_mod=wl.IMAGE),
+    "text_only": dict(Hq=2, Hkv=1, W=16, spans=((300,),)),
+    "multi_tile_1300": dict(Hq=4, Hkv=1, W=32, spans=((100, 500, 50, 600, 50),), pct=(7,)),
+    "batch_of_3": dict(Hq=4, Hkv=2, W=16, spans=((30, 260, 40), (64, 700, 69), (20, 100, 17)), pct=(10, 20, 5)),
+    "budget_equals_window": dict(Hq=2, Hkv=2, W=16, spans=((30, 200, 30),), budgets=(16,)),
+    "budget_equals_length": dict(Hq=2, Hkv=2, W=16, spans=((30, 200, 30),), budgets=(260,)),
+    "pivots_over_one_tile": dict(Hq=2, Hkv=1, W=32, spans=((60, 900, 64),), pct=(30,)),
+    "intra_forced": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), theta=2.0),
+    "cross_forced": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), theta=-1.0),
+    "gate_off": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), tau_factor=float("inf")),
+    "gate_drops_everything": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), tau_factor=-1.0),
+    "shortest": dict(Hq=1, Hkv=1, W=1, spans=((1,),), budgets=(1,), n_layers=1),
+    "tiny_3_tokens": dict(Hq=2, Hkv=1, W=2, spans=((1, 2),), budgets=(2,), n_layers=1),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL_CASES))
+def test_small_cases_match_oracle(oracle, name):
+    w = small(name, **SMALL_CASES[name])
+    print(f"case {name}: L={w.seqlens} B={w.budgets} dtype={w.dtype}", flush=True)
+    gpu = run_gpu(w)
+    rep = Report()
+    for l in range(w.n_layers):
+        check_layer(oracle, w, gpu, l, report=rep)
+    print(rep, flush=True)
+
+
+def test_config0_tiny_f32(oracle):
+    w = wl.config(0)
+    gpu = run_gpu(w)
+    rep = check_layer(oracle, w, gpu, 0)
+    print(rep, flush=True)
+    for theta in (-1.0, 2.0):
+        g2 = run_gpu(w, theta=theta)
+        assert (g2["mode"] == (1 if theta < 0 else 0)).all()
+        check_layer(oracle, w, g2, 0, theta=theta)
+
+
+def test_invariants_and_determinism():
+    w = small("inv", Hq=4, Hkv=2, spans=((37, 411, 83),), n_layers=3)
+    a = run_gpu(w)
+    b = run_gpu(w)
+    for k in a:
+        assert (a[k].view(np.uint32) == b[k].view(np.uint32)).all() if a[k].dtype == np.float32 else (a[k] == b[k]).all(), k
+    L, B = w.seqlens[0], w.budgets[0]
+    for l in range(w.n_layers):
+        for g in range(w.n_kv_heads):
+            assert abs(a["importance"][l][g].astype(np.float64).sum() - 1.0) < 1e-4
+            kept = a["kept_idx"][l][g]
+            asg = a["assign"][l][g]
+            assert len(set(kept.tolist())) == B
+            assert ((asg >= -1) & (asg < B)).all()
+            assert (asg[kept] == np.arange(B)).all()
+
+
+def test_full_budget_leaves_the_cache_unchanged():
+    w = small("full", Hq=2, Hkv=2, W=16, spans=((30, 200, 30),), budgets=(260,))
+    K, V, Q = upload(w)
+    gpu = run_gpu(w, tensors=(K, V, Q))
+    assert (gpu["K_out"] == K.float().cpu().numpy()).all()
+    assert (gpu["V_out"] == V.float().cpu().numpy()).all()
+    assert (gpu["n_dropped"] == 0).all()
+
+
+def test_packed_token_major_layout(oracle):
+    """The same cache stored [T][Hkv][d] (varlen layout) through the stride arguments."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    w = small("strided", Hq=4, Hkv=2, spans=((37, 300, 40),), n_layers=2)
+    K, V, Q = upload(w)
+    ref = run_gpu(w, tensors=(K, V, Q))
+    Lyr, Hkv, T, d = K.shape
+    Kt = K.permute(0, 2, 1, 3).contiguous()  # [Lyr][T][Hkv][d]
+    Vt = V.permute(0, 2, 1, 3).contiguous()
+    params = fb.Params(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.seqlens, w.budgets,
+                       w.spans, w.window, w.theta, w.tau, k_strides=(T * Hkv * d, d, Hkv * d))
+    bufs = fb.DeviceBuffers(params)
+    bufs.plan(Kt, Q)
+    bufs.merge(Kt, Vt)
+    torch.cuda.synchronize()
+    assert (bufs.assign.cpu().numpy() == ref["assign"]).all()
+    assert (bufs.K_out.float().cpu().numpy() == ref["K_out"]).all()
+    assert (bufs.V_out.float().cpu().numpy() == ref["V_out"]).all()
+
+
+def test_ragged_batch_equals_each_sequence_alone():
+    w = small("batch", Hq=4, Hkv=2, W=16, spans=((30, 260, 40), (64, 700, 69), (20, 100, 17)), pct=(10, 20, 5))
+    K, V, Q = upload(w)
+    full = run_gpu(w, tensors=(K, V, Q))
+    cu, cuk, W = w.cu_seqlens, w.cu_kept, w.window
+    for b in range(w.batch):
+        one = wl.Workload(name="one", dtype=w.dtype, seed=w.seed, n_layers=w.n_layers, n_q_heads=w.n_q_heads,
+                          n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, window=W, seqlens=[w.seqlens[b]],
+                          budgets=[w.budgets[b]], spans=[w.spans[b]], span_mu=[w.span_mu[b]], sinks=[w.sinks[b]],
+                          theta=w.theta, tau=[w.tau[b]])
+        t = (K[:, :, cu[b]:cu[b + 1]].contiguous(), V[:, :, cu[b]:cu[b + 1]].contiguous(),
+             Q[:, :, b * W:(b + 1) * W].contiguous())
+        alone = run_gpu(one, tensors=t)
+        assert (alone["assign"] == full["assign"][:, :, cu[b]:cu[b + 1]]).all()
+        assert (alone["kept_idx"] == full["kept_idx"][:, :, cuk[b]:cuk[b + 1]]).all()
+        assert (alone["K_out"] == full["K_out"][:, :, cuk[b]:cuk[b + 1]]).all()
+        assert (alone["V_out"] == full["V_out"][:, :, cuk[b]:cuk[b + 1]]).all()
+        assert (alone["rho"][:, 0] == full["rho"][:, b]).all()
+
+
+@pytest.mark.parametrize("cfg,n_layers,sample", [
+    (1, 32, [(0, [0, 17]), (31, [5])]),      # the benchmark configuration, full depth
+    (2, 2, [(1, [0, 3])]),
+    (3, 2, [(0, [2])]),
+    (4, 2, [(1, [1])]),
+])
+def test_benchmark_configs_sampled_units(oracle, cfg, n_layers, sample):
+    w = wl.config(cfg, n_layers=n_layers)
+    print(f"config {cfg}: {w.name} layers={n_layers} T={w.total_tokens}", flush=True)
+    gpu = run_gpu(w)
+    rep = Report()
+    for layer, heads in sample:
+        seqs = None if w.batch == 1 else [0, w.batch - 1]
+        check_layer(oracle, w, gpu, layer, kv_heads=heads, seqs=seqs, report=rep)
+        print(f"  layer {layer} heads {heads}: {rep}", flush=True)
+    # properties that hold at any size, over the whole result
+    cu, cuk = w.cu_seqlens, w.cu_kept
+    for b in range(w.batch):
+        L, B = w.seqlens[b], w.budgets[b]
+        imp = gpu["importance"][:, :, cu[b]:cu[b + 1]].astype(np.float64)
+        assert np.abs(imp.sum(axis=-1) - 1.0).max() < 1e-3
+        kept = gpu["kept_idx"][:, :, cuk[b]:cuk[b + 1]]
+        assert (np.diff(kept, axis=-1) > 0).all() and kept.min() >= 0 and kept.max() < L
+        asg = gpu["assign"][:, :, cu[b]:cu[b + 1]]
+        assert ((asg >= -1) & (asg < B)).all()
+        own = np.take_along_axis(asg, kept, axis=-1)
+        assert (own == np.arange(B)).all()
+        assert ((asg == -1).sum(axis=-1) == gpu["n_dropped"][:, :, b]).all()
