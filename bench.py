@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlowMM prefill-time KV-cache merge on one MI355X.
+
+A step is one pass of the whole hot path (flowmm_plan + flowmm_merge: score, flow, select,
+match, merge) over every layer and head of one synthetic prefill cache that already sits in
+HBM.  Prints ONE JSON line: tokens merged per second, the roofline of the dominant kernel
+(timed live with HIP events on the launch stream) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(wl):
+    """Bytes each step of the method must move, per full pass, from the shapes alone.
+
+    whole pass (a fused implementation): K twice (before and after the top-B split), V once,
+    compacted rows written once, Q window, importance written+read and assign written:
+    3 L d s + 2 B d s + G W d s + 12 L per (sequence, layer, kv head).
+    Per kernel: what that kernel's own inputs and outputs amount to at the library boundary."""
+    s = 2 if wl.dtype == "bf16" else 4
+    d, G, W = wl.head_dim, wl.group, wl.window
+    units = wl.n_layers * wl.n_kv_heads
+    tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match", "merge_tasks", "select",
+                          "merge_csr")}
+    for L, B in zip(wl.seqlens, wl.budgets):
+        row = d * s
+        tot["whole_pass"] += units * (3 * L * row + 2 * B * row + G * W * row + 12 * L)
+        tot["score_stats"] += units * (L * row + G * W * row)              # K once, Q window
+        tot["score_colsum"] += units * (L * row + G * W * row + 4 * L)     # K once, Q, importance out
+        tot["select"] += units * (4 * L + 4 * L + 4 * B)                   # importance in, assign + kept out
+        tot["match"] += units * (L * row + 4 * L + 4 * L + 4 * B)          # K once, assign in/out, kept
+        tot["merge_csr"] += units * (4 * L + 4 * (L - B))                  # assign in, member list out
+        tot["merge_tasks"] += units * (2 * L * row + 2 * B * row + 4 * (L - B))  # K and V rows in, compacted out
+    return tot
+
+
+def cpu_baseline(wl, budget_s: float):
+    """Time the CPU oracle (as it stands) on whole layers of the same workload."""
+    import oracle
+    oracle.build()
+    done, t_total = 0, 0.0
+    while done < wl.n_layers and (done == 0 or t_total + t_total / done <= budget_s):
+        K, V, Q = wl.layer_tensors(done)
+        t0 = time.perf_counter()
+        for b in range(wl.batch):
+            sl = wl.seq_slice(b)
+            W = wl.window
+            oracle.layer_pass(K[:, sl], V[:, sl], Q[:, b * W:(b + 1) * W], wl.modality(b), wl.budgets[b],
+                              wl.dtype, wl.theta, wl.tau[b])
+        t_total += time.perf_counter() - t0
+        done += 1
+    t_full = t_total * wl.n_layers / done
+    return {"value": wl.total_tokens / t_full, "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"layers 0..{done - 1} of {wl.n_layers} (all heads, all sequences), {t_total:.2f} s, "
+                      f"scaled linearly to the full depth"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the metric's configuration)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
+    ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    from paper_2511_05534_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    fb.load(build_if_missing=False)
+    wl = workloads.config(args.config)
+    dev = "cuda:0"
+    K, V, Q = fb.upload_workload(wl, dev)
+    params = fb.Params.from_workload(wl)
+    bufs = fb.DeviceBuffers(params, dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        bufs.plan(K, Q, stream)
+        bufs.merge(K, V, stream)
+
+    # warm-up; its last steps are bracketed kernel by kernel to find the dominant one
+    for _ in range(max(args.warmup - 5, 0)):
+        step()
+    torch.cuda.synchronize()
+    fb.flowmm_profile_select("all")
+    for _ in range(min(5, max(args.warmup, 1))):
+        step()
+    torch.cuda.synchronize()
+    per_kernel = fb.flowmm_profile_collect()
+    kernels_us = {k: 1e3 * ms / n for k, (ms, n) in per_kernel.items()}
+    dominant = args.kernel or max(kernels_us, key=kernels_us.get)
+
+    # timed region: exactly K steps; only the dominant kernel carries events
+    fb.flowmm_profile_select(dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    t_host = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_n = fb.flowmm_profile_collect()[dominant]
+    fb.flowmm_profile_select("")
+
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    tokens_per_s = wl.total_tokens / (ms_per_step * 1e-3)
+    alg = algorithmic_bytes(wl)
+    dom_us = 1e3 * dom_ms / dom_n
+    achieved = alg.get(dominant, 0) / (dom_us * 1e-6) / 1e9
+    out = {
+        "metric": "KV tokens merged/sec per GPU + achieved HBM GB/s (% of peak), full prefill cache",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {wl.name}", "layers": wl.n_layers, "q_heads": wl.n_q_heads,
+                   "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "seqlens": wl.seqlens, "budgets": wl.budgets,
+                   "window": wl.window, "theta": wl.theta, "tokens_per_step": wl.total_tokens,
+                   "token_layer_kvheads_per_s": tokens_per_s * wl.n_layers * wl.n_kv_heads},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_us": dom_us, "algorithmic_bytes_per_launch": alg.get(dominant, 0)},
+        "full_pass": {"algorithmic_bytes": alg["whole_pass"],
+                      "achieved_GBs": alg["whole_pass"] / (ms_per_step * 1e-3) / 1e9,
+                      "frac_of_hbm_peak": alg["whole_pass"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "host_enqueue_us_per_step": 1e6 * t_host / args.steps},
+        "kernels_us": kernels_us,
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -108,6 +108,18 @@ flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *pl
 /* Message of the last failing call on this thread (static storage, never NULL). */
 const char *flowmm_last_error(void);
 
+/* ---- measurement support (no part of the method; used by the benchmark) --------------------
+ * The library can bracket chosen kernels with HIP events on the launch stream.
+ * flowmm_profile_select: names = "all", "" / NULL (off, the default) or a comma-separated list
+ *   of kernel names as returned by flowmm_profile_kernel_name(0 .. count-1).
+ * flowmm_profile_collect: waits for the recorded events (host-side wait on those events only),
+ *   adds up milliseconds and launch counts per kernel id into the two host arrays (each
+ *   flowmm_profile_kernel_count() long, either may be NULL) and forgets the records. */
+int flowmm_profile_kernel_count(void);
+const char *flowmm_profile_kernel_name(int id);
+void flowmm_profile_select(const char *names);
+flowmm_status flowmm_profile_collect(double *total_ms, long long *launches);
+
 #ifdef __cplusplus
 }
 #endif

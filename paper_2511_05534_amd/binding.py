@@ -18,7 +18,9 @@ FLOWMM_OK, FLOWMM_EINVAL, FLOWMM_EUNSUPPORTED, FLOWMM_EWORKSPACE, FLOWMM_EHIP = 
 FLOWMM_F32, FLOWMM_BF16 = 0, 1
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
-EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_last_error")
+EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_last_error",
+           "flowmm_profile_kernel_count", "flowmm_profile_kernel_name", "flowmm_profile_select",
+           "flowmm_profile_collect")
 
 
 class flowmm_span(C.Structure):
@@ -68,8 +70,14 @@ def load(build_if_missing: bool = True):
                                     C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_size_t, C.c_void_p]
         lib.flowmm_merge.argtypes = [C.POINTER(flowmm_params), C.POINTER(flowmm_plan_buffers), C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-        for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge):
+        for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge, lib.flowmm_profile_collect,
+                  lib.flowmm_profile_kernel_count):
             f.restype = C.c_int
+        lib.flowmm_profile_kernel_name.restype = C.c_char_p
+        lib.flowmm_profile_kernel_name.argtypes = [C.c_int]
+        lib.flowmm_profile_select.argtypes = [C.c_char_p]
+        lib.flowmm_profile_select.restype = None
+        lib.flowmm_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
         _lib = lib
     return _lib
 
@@ -147,7 +155,35 @@ def flowmm_merge(params: Params, plan_ptrs: Sequence[int], K: int, V: int, K_out
                                C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
+def flowmm_profile_select(names: str = ""):
+    load().flowmm_profile_select(names.encode())
+
+
+def flowmm_profile_collect():
+    """-> {kernel name: (total milliseconds, launches)} for the kernels bracketed since the last call."""
+    lib = load()
+    n = lib.flowmm_profile_kernel_count()
+    ms = (C.c_double * n)()
+    cnt = (C.c_longlong * n)()
+    _check(lib.flowmm_profile_collect(ms, cnt))
+    return {lib.flowmm_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}
+
+
 # ---- device-memory plumbing (PyTorch owns the memory; nothing below computes) ------------------
+def upload_workload(wl, device="cuda:0", layers=None):
+    """K, V [Lyr][Hkv][T][d] and Q [Lyr][Hq][batch*W][d] of a synthetic workload as device tensors."""
+    import torch
+    layers = range(wl.n_layers) if layers is None else layers
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    Ks, Vs, Qs = [], [], []
+    for l in layers:
+        k, v, q = wl.layer_tensors(l)  # float32 values that are exact in the workload dtype
+        Ks.append(torch.from_numpy(k).to(device).to(tdt))
+        Vs.append(torch.from_numpy(v).to(device).to(tdt))
+        Qs.append(torch.from_numpy(q).to(device).to(tdt))
+    return torch.stack(Ks), torch.stack(Vs), torch.stack(Qs)
+
+
 class DeviceBuffers:
     """Plan buffers, outputs and workspace for one Params, allocated with torch on `device`."""
 

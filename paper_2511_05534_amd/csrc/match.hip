@@ -10,6 +10,7 @@
 // norm is a positive factor common to all its candidates and is left out of the comparison.
 #include "device_common.h"
 #include "kernels.h"
+#include "profile.h"
 
 namespace flowmm {
 
@@ -135,6 +136,7 @@ __global__ __launch_bounds__(kThreads) void match_kernel(Ctx c) {
 
 template <bool BF16, int D>
 hipError_t launch_match_t(const Ctx &c) {
+  ProfScope ps(c.stream, KID_MATCH);
   match_kernel<BF16, D><<<dim3(c.sh.tiles_match, c.sh.Hkv, c.sh.n_layers), kThreads, 0, c.stream>>>(c);
   return hipGetLastError();
 }

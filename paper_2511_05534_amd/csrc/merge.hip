@@ -13,6 +13,7 @@
 //   3. fold  : slots with several tasks add up their partials in task order.
 #include "device_common.h"
 #include "kernels.h"
+#include "profile.h"
 
 namespace flowmm {
 
@@ -286,9 +287,18 @@ hipError_t launch_merge_t(const Ctx &c, int nw_shift, size_t lds) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_csr_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  merge_csr_kernel<<<dim3(sh.batch, sh.Hkv, sh.n_layers), kCsrThreads, lds, c.stream>>>(c, nw_shift);
-  merge_tasks_kernel<BF16, D><<<dim3((sh.tasks_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
-  merge_fold_kernel<BF16, D><<<dim3((sh.multi_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+  {
+    ProfScope ps(c.stream, KID_MERGE_CSR);
+    merge_csr_kernel<<<dim3(sh.batch, sh.Hkv, sh.n_layers), kCsrThreads, lds, c.stream>>>(c, nw_shift);
+  }
+  {
+    ProfScope ps(c.stream, KID_MERGE_TASKS);
+    merge_tasks_kernel<BF16, D><<<dim3((sh.tasks_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+  }
+  {
+    ProfScope ps(c.stream, KID_MERGE_FOLD);
+    merge_fold_kernel<BF16, D><<<dim3((sh.multi_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+  }
   return hipGetLastError();
 }
 

@@ -3,6 +3,7 @@
 // the modality spans into one byte per packed token.
 #include "device_common.h"
 #include "kernels.h"
+#include "profile.h"
 
 namespace flowmm {
 
@@ -34,9 +35,13 @@ hipError_t launch_meta_upload(const Ctx &c, const int *words, int n_words, bool 
     MetaChunk chunk;
     const int n = n_words - off < kMetaChunkWords ? n_words - off : kMetaChunkWords;
     for (int i = 0; i < n; ++i) chunk.w[i] = words[off + i];
+    ProfScope ps(c.stream, KID_META_UPLOAD);
     meta_upload_kernel<<<1, 256, 0, c.stream>>>(chunk, c.meta + off, n);
   }
-  if (expand_modality) expand_modality_kernel<<<words[MW_N_SPANS], 256, 0, c.stream>>>(c.meta, c.mod);
+  if (expand_modality) {
+    ProfScope ps(c.stream, KID_EXPAND_MODALITY);
+    expand_modality_kernel<<<words[MW_N_SPANS], 256, 0, c.stream>>>(c.meta, c.mod);
+  }
   return hipGetLastError();
 }
 

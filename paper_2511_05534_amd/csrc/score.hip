@@ -10,6 +10,7 @@
 // MFMA operand registers (one 16-byte chunk per lane and k step).
 #include "device_common.h"
 #include "kernels.h"
+#include "profile.h"
 
 namespace flowmm {
 
@@ -272,9 +273,18 @@ hipError_t launch_score_t(const Ctx &c) {
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3);
   if (e != hipSuccess) return e;
   const dim3 grid(sh.tiles_score, sh.Hkv, sh.n_layers);
-  score_stats_kernel<BF16, D><<<grid, kThreads, lds1, c.stream>>>(c);
-  score_combine_kernel<<<dim3(sh.batch, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
-  score_colsum_kernel<BF16, D><<<grid, kThreads, lds3, c.stream>>>(c);
+  {
+    ProfScope ps(c.stream, KID_SCORE_STATS);
+    score_stats_kernel<BF16, D><<<grid, kThreads, lds1, c.stream>>>(c);
+  }
+  {
+    ProfScope ps(c.stream, KID_SCORE_COMBINE);
+    score_combine_kernel<<<dim3(sh.batch, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+  }
+  {
+    ProfScope ps(c.stream, KID_SCORE_COLSUM);
+    score_colsum_kernel<BF16, D><<<grid, kThreads, lds3, c.stream>>>(c);
+  }
   return hipGetLastError();
 }
 

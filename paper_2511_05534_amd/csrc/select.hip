@@ -10,6 +10,7 @@
 // order like the values); a block-wide ordered scan then compacts the pivots.
 #include "device_common.h"
 #include "kernels.h"
+#include "profile.h"
 
 namespace flowmm {
 
@@ -168,6 +169,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
 }  // namespace
 
 hipError_t launch_select(const Ctx &c) {
+  ProfScope ps(c.stream, KID_SELECT);
   select_kernel<<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kThreads, 0, c.stream>>>(c);
   return hipGetLastError();
 }

@@ -15,17 +15,8 @@ ATOL_OUT = {"bf16": 2e-2, "f32": 1e-5}  # merged K/V max-abs error
 
 
 def upload(wl, device="cuda:0", layers=None):
-    """K, V [Lyr][Hkv][T][d], Q [Lyr][Hq][batch*W][d] as torch tensors of the workload dtype."""
-    import torch
-    layers = range(wl.n_layers) if layers is None else layers
-    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
-    Ks, Vs, Qs = [], [], []
-    for l in layers:
-        k, v, q = wl.layer_tensors(l)
-        Ks.append(torch.from_numpy(k).to(device).to(tdt))
-        Vs.append(torch.from_numpy(v).to(device).to(tdt))
-        Qs.append(torch.from_numpy(q).to(device).to(tdt))
-    return torch.stack(Ks), torch.stack(Vs), torch.stack(Qs)
+    from paper_2511_05534_amd import binding as fb
+    return fb.upload_workload(wl, device, layers)
 
 
 def run_gpu(wl, theta=None, tau=None, device="cuda:0", tensors=None):
