@@ -49,6 +49,11 @@ typedef enum { FLOWMM_F32 = 0, FLOWMM_BF16 = 1 } flowmm_dtype;
 
 enum { FLOWMM_TEXT = 0, FLOWMM_IMAGE = 1 };
 enum { FLOWMM_MODE_INTRA = 0, FLOWMM_MODE_CROSS = 1 };
+/* Short bf16 prompts (every L <= 1024, (Hq/Hkv) * window padded to 32 <= 64, every B <= 256) are
+ * handled by kernels that keep a whole (sequence, layer, kv head) inside one workgroup; this flag
+ * sends them through the general multi-workgroup kernels instead (same results up to fp32
+ * summation order; used by tests). */
+enum { FLOWMM_FLAG_GENERIC_PATH = 1 };
 
 /* Half-open token range [begin, end) local to its sequence, with its modality. */
 typedef struct {
@@ -71,6 +76,7 @@ typedef struct {
                                               +inf disables the gate, a negative value drops everything */
   int64_t k_stride_layer, k_stride_head, k_stride_token; /* elements; the same strides address V */
   int64_t q_stride_layer, q_stride_head, q_stride_token;
+  int32_t flags;                           /* 0, or FLOWMM_FLAG_* bits */
 } flowmm_params;
 
 /* The plan: device buffers the caller allocates; flowmm_plan fills them, flowmm_merge reads

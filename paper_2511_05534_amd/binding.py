@@ -16,6 +16,7 @@ from . import build as _build
 
 FLOWMM_OK, FLOWMM_EINVAL, FLOWMM_EUNSUPPORTED, FLOWMM_EWORKSPACE, FLOWMM_EHIP = range(5)
 FLOWMM_F32, FLOWMM_BF16 = 0, 1
+FLOWMM_FLAG_GENERIC_PATH = 1
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
 EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_last_error",
@@ -37,6 +38,7 @@ class flowmm_params(C.Structure):
         ("tau", C.POINTER(C.c_float)),
         ("k_stride_layer", C.c_int64), ("k_stride_head", C.c_int64), ("k_stride_token", C.c_int64),
         ("q_stride_layer", C.c_int64), ("q_stride_head", C.c_int64), ("q_stride_token", C.c_int64),
+        ("flags", C.c_int32),
     ]
 
 
@@ -95,7 +97,7 @@ class Params:
                  spans: Sequence[Sequence[Tuple[int, int, int]]], window: int, theta: float,
                  tau: Sequence[float], scale: float = 0.0,
                  k_strides: Tuple[int, int, int] | None = None,
-                 q_strides: Tuple[int, int, int] | None = None):
+                 q_strides: Tuple[int, int, int] | None = None, flags: int = 0):
         self.batch = len(seqlens)
         self.seqlens = [int(x) for x in seqlens]
         self.budgets = [int(x) for x in budgets]
@@ -118,14 +120,15 @@ class Params:
             self.batch, self._cu.ctypes.data_as(C.POINTER(C.c_int32)),
             self._bud.ctypes.data_as(C.POINTER(C.c_int32)), self._spans,
             self._cu_spans.ctypes.data_as(C.POINTER(C.c_int32)), W, float(scale), float(theta),
-            self._tau.ctypes.data_as(C.POINTER(C.c_float)), *k_strides, *q_strides)
+            self._tau.ctypes.data_as(C.POINTER(C.c_float)), *k_strides, *q_strides, int(flags))
         self.n_layers, self.n_q_heads, self.n_kv_heads, self.head_dim, self.window = \
             n_layers, n_q_heads, n_kv_heads, head_dim, W
 
     @classmethod
-    def from_workload(cls, wl, theta: float | None = None, tau: Sequence[float] | None = None):
+    def from_workload(cls, wl, theta: float | None = None, tau: Sequence[float] | None = None, flags: int = 0):
         return cls(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.seqlens, wl.budgets,
-                   wl.spans, wl.window, wl.theta if theta is None else theta, wl.tau if tau is None else tau)
+                   wl.spans, wl.window, wl.theta if theta is None else theta, wl.tau if tau is None else tau,
+                   flags=flags)
 
 
 def flowmm_plan_sizes(params: Params):

@@ -54,6 +54,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   if (p->window < 1) return fail(FLOWMM_EINVAL, "window must be >= 1");
   if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return fail(FLOWMM_EINVAL, "scale must be finite and >= 0");
   if (std::isnan(p->theta)) return fail(FLOWMM_EINVAL, "theta is NaN");
+  if (p->flags & ~FLOWMM_FLAG_GENERIC_PATH) return fail(FLOWMM_EINVAL, "unknown bits in flags");
   if (p->cu_seqlens[0] != 0 || p->cu_spans[0] != 0) return fail(FLOWMM_EINVAL, "cu_seqlens[0] and cu_spans[0] must be 0");
 
   const int es = p->dtype == FLOWMM_BF16 ? 2 : 4;
@@ -82,7 +83,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
       cu_multi(batch + 1, 0), cu_part(batch + 1, 0);
   std::vector<int32_t> seq((size_t)batch * SW_WORDS, 0);
   int64_t sumB = 0;
-  int maxB = 0;
+  int maxB = 0, maxL = 0, maxE = 0;
   for (int b = 0; b < batch; ++b) {
     const int64_t L64 = (int64_t)p->cu_seqlens[b + 1] - p->cu_seqlens[b];
     if (L64 < 1) return fail(FLOWMM_EINVAL, "cu_seqlens must be strictly increasing (sequence %d)", b);
@@ -116,12 +117,17 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     r[SW_SPAN_OFF] = s0; r[SW_N_SPANS] = s1 - s0; r[SW_WIN_HAS_IMG] = win_img;
     sumB += B;
     if (B > maxB) maxB = B;
+    if (L > maxL) maxL = L;
+    if (E > maxE) maxE = E;
   }
   const int64_t T = p->cu_seqlens[batch];
   const int n_spans = p->cu_spans[batch];
   const int64_t units = (int64_t)sh.n_layers * sh.Hkv;
   if (units * T >= (int64_t)1 << 40) return fail(FLOWMM_EUNSUPPORTED, "cache too large");
-  sh.T = (int)T; sh.SB = (int)sumB; sh.maxB = maxB;
+  sh.T = (int)T; sh.SB = (int)sumB; sh.maxB = maxB; sh.maxL = maxL; sh.maxE = maxE;
+  sh.unit_path = !(p->flags & FLOWMM_FLAG_GENERIC_PATH) && unit_path_fits(sh);
+  if (sh.unit_path)  // one score tile per sequence: its workgroup sees every key
+    for (int b = 0; b <= batch; ++b) cu_score[b] = b;
   sh.tiles_score = cu_score[batch]; sh.tiles_match = cu_match[batch];
   sh.tasks_total = cu_task[batch]; sh.multi_total = cu_multi[batch]; sh.part_total = cu_part[batch];
   if (score_lds_bytes(sh) > kLdsLimit)
@@ -261,6 +267,10 @@ FLOWMM_API flowmm_status flowmm_plan(const flowmm_params *p, const void *K, cons
   c.K = K; c.Q = Q_window;
   hipError_t e;
   if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if (c.sh.unit_path) {
+    if ((e = launch_unit_plan(c)) != hipSuccess) return hip_fail(e, "unit-resident plan kernels");
+    return FLOWMM_OK;
+  }
   if ((e = launch_score(c)) != hipSuccess) return hip_fail(e, "score kernels");
   if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
   if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
@@ -293,7 +303,7 @@ FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_
   c.K = K; c.V = V; c.K_out = K_out; c.V_out = V_out;
   hipError_t e;
   if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), false)) != hipSuccess) return hip_fail(e, "metadata upload");
-  if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
+  if ((e = c.sh.unit_path ? launch_unit_merge(c) : launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
   return FLOWMM_OK;
 }
 

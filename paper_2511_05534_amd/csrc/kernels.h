@@ -42,6 +42,11 @@ hipError_t launch_select(const Ctx &c);   // flow + top-B split
 hipError_t launch_match(const Ctx &c);
 hipError_t launch_merge(const Ctx &c);    // CSR build, task sums, combine
 
+// unit-resident path (short prompts): one workgroup per (sequence, kv head, layer)
+bool unit_path_fits(const Shape &sh);
+hipError_t launch_unit_plan(const Ctx &c);   // score+select, flow+match
+hipError_t launch_unit_merge(const Ctx &c);
+
 // static LDS needs, used by the host to reject shapes that cannot be staged
 size_t score_lds_bytes(const Shape &sh);
 size_t merge_csr_lds_bytes(int max_budget);

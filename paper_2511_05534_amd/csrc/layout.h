@@ -48,7 +48,8 @@ constexpr int kCsrWaves = 16;                                // waves of the CSR
 
 struct Shape {
   int n_layers, Hq, Hkv, G, d, bf16;
-  int batch, T, SB, W, W_pad, R_pad, maxB;
+  int batch, T, SB, W, W_pad, R_pad, maxB, maxL, maxE;
+  int unit_path;  // 1: every unit is handled by one workgroup (unit_path.hip)
   int tiles_score, tiles_match, tasks_total, multi_total, part_total;
   float scale_log2e, theta;
   long long ks_layer, ks_head, ks_tok;  // K/V strides in 16-byte chunks

@@ -11,52 +11,20 @@
 #include "device_common.h"
 #include "kernels.h"
 #include "profile.h"
+#include "select_core.h"
 
 namespace flowmm {
 
 namespace {
 
 constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
-
-// exclusive prefix sum over the workgroup, in thread order; *total receives the block sum
-__device__ __forceinline__ int block_exclusive_scan(int v, int *lds_wave /*[kWaves+1]*/, int *total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int u = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += u;
-  }
-  __syncthreads();  // lds_wave may still be read from a previous call
-  if (lane == 63) lds_wave[wave] = inc;
-  __syncthreads();
-  if (wave == 0) {
-    int w = lane < kWaves ? lds_wave[lane] : 0;
-    int winc = w;
-#pragma unroll
-    for (int o = 1; o < kWaves; o <<= 1) {
-      const int u = __shfl_up(winc, o, 64);
-      if (lane >= o) winc += u;
-    }
-    if (lane < kWaves) lds_wave[lane] = winc - w;
-    if (lane == kWaves - 1) lds_wave[kWaves] = winc;
-  }
-  __syncthreads();
-  *total = lds_wave[kWaves];
-  return lds_wave[wave] + inc - v;
-}
 
 __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
-  __shared__ int hist[256];
-  __shared__ int lds_wave[kWaves + 1];
-  __shared__ unsigned sh_prefix;
-  __shared__ int sh_remaining;
+  __shared__ SelectScratch<kThreads> scratch;
   __shared__ float lds_head[kThreads];
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
   const SeqInfo s = load_seq(c.meta, b);
-  const int lane = threadIdx.x & 63;
 
   // ---- flow (one workgroup per sequence and layer does it) ------------------------------
   if (gkv == 0) {
@@ -87,83 +55,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
   }
   if (threadIdx.x == 0) c.n_dropped[(l * sh.Hkv + gkv) * sh.batch + b] = 0;
 
-  // ---- B-th largest importance among the non-proxy tokens ---------------------------------
+  // ---- top-B split -----------------------------------------------------------------------------
   const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) +
                         (long long)(l * sh.Hkv + gkv) * sh.T + s.tok_off;
-  const int nbody = s.L - sh.W;
-  const int need = s.B - sh.W;  // pivots still to choose among the body tokens
-  unsigned thr = 0xffffffffu;   // nothing in the body exceeds or equals this
-  int need_eq = 0;
-  if (need > 0) {
-    unsigned prefix = 0, mask = 0;
-    int remaining = need;
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      if (threadIdx.x < 256) hist[threadIdx.x] = 0;
-      __syncthreads();
-      for (int i0 = 0; i0 < nbody; i0 += kThreads) {
-        const int i = i0 + threadIdx.x;
-        const unsigned k = i < nbody ? imp[i] : 0u;
-        const bool act = i < nbody && (k & mask) == prefix;
-        const int dg = (k >> shift) & 255;
-        const unsigned long long am = __ballot(act);
-        if (am) {
-          const int first = __ffsll((long long)am) - 1;
-          const int d0 = __shfl(dg, first, 64);
-          if (__ballot(act && dg == d0) == am) {
-            if (lane == first) atomicAdd(&hist[d0], __popcll(am));
-          } else if (act) {
-            atomicAdd(&hist[dg], 1);
-          }
-        }
-      }
-      __syncthreads();
-      // bins in descending order: thread t looks at bin 255 - t
-      const int cnt = threadIdx.x < 256 ? hist[255 - threadIdx.x] : 0;
-      int total;
-      const int before = block_exclusive_scan(cnt, lds_wave, &total);
-      if (threadIdx.x < 256 && before < remaining && remaining <= before + cnt) {
-        sh_prefix = prefix | ((unsigned)(255 - threadIdx.x) << shift);
-        sh_remaining = remaining - before;
-      }
-      __syncthreads();
-      prefix = sh_prefix;
-      remaining = sh_remaining;
-      mask |= 255u << shift;
-    }
-    thr = prefix;
-    need_eq = remaining;  // how many tokens equal to the threshold are still pivots
-  }
-
-  // ---- ordered compaction -------------------------------------------------------------------
   int *kept = c.kept_idx + (long long)(l * sh.Hkv + gkv) * sh.SB + s.kept_off;
   int *assign = c.assign + (long long)(l * sh.Hkv + gkv) * sh.T + s.tok_off;
-  int gt_carry = 0, eq_carry = 0;
-  for (int i0 = 0; i0 < s.L; i0 += kThreads) {
-    const int i = i0 + threadIdx.x;
-    int gt = 0, eq = 0;
-    if (i < s.L) {
-      if (i >= nbody) {
-        gt = 1;
-      } else {
-        const unsigned k = imp[i];
-        gt = k > thr;
-        eq = k == thr;
-      }
-    }
-    int total;
-    const int before = block_exclusive_scan(gt | (eq << 16), lds_wave, &total);
-    const int gt_before = gt_carry + (before & 0xffff);
-    const int eq_before = eq_carry + (before >> 16);
-    if (i < s.L) {
-      const bool is_kept = gt || (eq && eq_before < need_eq);
-      const int slot = gt_before + min(eq_before, need_eq);
-      if (is_kept) kept[slot] = i;
-      assign[i] = is_kept ? slot : -2;  // -2: to be matched
-    }
-    gt_carry += total & 0xffff;
-    eq_carry += total >> 16;
-  }
+  select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
 }
 
 }  // namespace

@@ -1,0 +1,616 @@
+// Unit-resident path for short prompts (bf16, every L <= 1024, G*W_pad <= 64, every B <= 256).
+//
+// When one (sequence, layer, kv head) unit fits on a compute unit, the whole logits tile
+// (G*W rows x L keys) stays in MFMA accumulator registers, so the softmax needs no second pass
+// over K and no partial statistics in HBM, and every step of a unit runs inside one workgroup:
+//   unit_score_select : score + top-B split            (K read once)
+//   unit_match        : flow + cosine argmax            (K read once, pivots staged once)
+//   unit_merge        : counting sort + segment sums    (K and V read once)
+// Three launches instead of ten.  The arithmetic is the same as in the generic kernels
+// (score.hip, select.hip, match.hip, merge.hip); see those files for the paper passages.
+#include "device_common.h"
+#include "kernels.h"
+#include "profile.h"
+#include "select_core.h"
+
+namespace flowmm {
+
+namespace {
+
+constexpr bool kBF16 = true;
+
+// ============================ score + select ================================================
+constexpr int kF1Threads = 512;
+constexpr int kF1Waves = kF1Threads / 64;
+
+template <int D, int RB, int NT>
+__global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
+  using CF = Cfg<kBF16, D>;
+  constexpr int NCH = CF::NCH, NF = CF::NF;
+  constexpr int ROWS = RB * 32;
+  constexpr int LMAX = NT * kF1Waves * 32;
+  __shared__ uint4 ldsq[ROWS * (NCH + 1)];
+  __shared__ float lds_stat[kF1Waves][ROWS];
+  __shared__ float lds_gstat[ROWS];
+  __shared__ float lds_rowimg[ROWS];
+  __shared__ float lds_cross[kF1Waves][RB];
+  __shared__ unsigned lds_keys[LMAX];
+  __shared__ SelectScratch<kF1Threads> scratch;
+
+  const Shape &sh = c.sh;
+  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const SeqInfo s = load_seq(c.meta, b);
+  const int L = s.L;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+  const long long unit = (long long)l * sh.Hkv + gkv;
+  const uint8_t *mod = c.mod + s.tok_off;
+
+  // stage the query rows (zero rows pad every head to a multiple of 32)
+  {
+    const uint4 *Q = reinterpret_cast<const uint4 *>(c.Q) + (long long)l * sh.qs_layer;
+    for (int idx = threadIdx.x; idx < ROWS * NCH; idx += kF1Threads) {
+      const int row = idx / NCH, ch = idx - row * NCH;
+      const int g = row / sh.W_pad, r = row - g * sh.W_pad;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (r < sh.W) v = Q[(long long)(gkv * sh.G + g) * sh.qs_head + (long long)(b * sh.W + r) * sh.qs_tok + ch];
+      ldsq[row * (NCH + 1) + ch] = v;
+    }
+    for (int row = threadIdx.x; row < ROWS; row += kF1Threads) {
+      const int r = row % sh.W_pad;
+      lds_rowimg[row] = (r < sh.W && mod[L - sh.W + r]) ? 1.f : 0.f;
+    }
+  }
+  __syncthreads();
+
+  // logits of this wave's key tiles: wave w owns tiles w, w+8, ... (32 keys each)
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
+                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  f32x16_t acc[NT][RB];
+  int keymod[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[j][rb][i] = 0.f;
+    const int key0 = (wave + kF1Waves * j) * 32;
+    keymod[j] = 0;
+    if (key0 < L) {
+      const int key = min(key0 + n, L - 1);
+      keymod[j] = mod[key];
+      const uint4 *row = K + (long long)key * sh.ks_tok + half;
+      uint4 kf[NF];
+#pragma unroll
+      for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
+#pragma unroll
+      for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          mma_chunk<kBF16>(acc[j][rb], ldsq[(rb * 32 + n) * (NCH + 1) + 2 * f + half], kf[f]);  // [query row][key]
+    }
+  }
+
+  // mask, move to the log2 domain, per-row maximum over this wave's keys
+  const float cl = sh.scale_log2e;
+  float rowv[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = (rb * 32 + acc_row(i, half)) % sh.W_pad;
+      const int limit = r < sh.W ? L - sh.W + r : -1;
+      float m = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int key = (wave + kF1Waves * j) * 32 + n;
+        const float v = key <= limit ? acc[j][rb][i] * cl : -INFINITY;
+        acc[j][rb][i] = v;
+        m = fmaxf(m, v);
+      }
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+      rowv[rb][i] = m;
+    }
+  if (n == 0) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) lds_stat[wave][rb * 32 + acc_row(i, half)] = rowv[rb][i];
+  }
+  __syncthreads();
+  if (threadIdx.x < ROWS) {
+    float m = lds_stat[0][threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < kF1Waves; ++w) m = fmaxf(m, lds_stat[w][threadIdx.x]);
+    lds_gstat[threadIdx.x] = m == -INFINITY ? 0.f : m;  // padding rows: every logit is -inf
+  }
+  __syncthreads();
+
+  // exponentials and per-row sums
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float M = lds_gstat[rb * 32 + acc_row(i, half)];
+      float z = 0.f;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const float e = fast_exp2(acc[j][rb][i] - M);
+        acc[j][rb][i] = e;
+        z += e;
+      }
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) z += __shfl_xor(z, o, 64);
+      rowv[rb][i] = z;
+    }
+  if (n == 0) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) lds_stat[wave][rb * 32 + acc_row(i, half)] = rowv[rb][i];
+  }
+  __syncthreads();
+  if (threadIdx.x < ROWS) {
+    float z = 0.f;
+#pragma unroll
+    for (int w = 0; w < kF1Waves; ++w) z += lds_stat[w][threadIdx.x];
+    lds_gstat[threadIdx.x] = z > 0.f ? 1.0f / z : 0.f;
+  }
+  __syncthreads();
+
+  // probabilities reduced over the query rows: importance per key, cross-modal mass per head
+  const float inv_rows = 1.0f / (float)(sh.G * sh.W);
+  float *imp = c.importance + unit * sh.T + s.tok_off;
+  float cross_acc[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) cross_acc[rb] = 0.f;
+  float invz[RB][16], wimg[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      invz[rb][i] = lds_gstat[rb * 32 + acc_row(i, half)];
+      wimg[rb][i] = lds_rowimg[rb * 32 + acc_row(i, half)];
+    }
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    float colsum = 0.f;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      float bs = 0.f, bsi = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = acc[j][rb][i] * invz[rb][i];
+        bs += p;
+        bsi = fmaf(p, wimg[rb][i], bsi);
+      }
+      colsum += bs;
+      cross_acc[rb] += keymod[j] ? bs - bsi : bsi;  // mass on keys of the other modality
+    }
+    const float tot = (colsum + __shfl_xor(colsum, 32, 64)) * inv_rows;
+    const int key = (wave + kF1Waves * j) * 32 + n;
+    if (half == 0 && key < L) {
+      imp[key] = tot;
+      lds_keys[key] = __float_as_uint(tot);
+    }
+  }
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const float v = wave_sum(cross_acc[rb]);
+    if (lane == 0) lds_cross[wave][rb] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < sh.G) {
+    // head g owns the row blocks [g*W_pad/32, (g+1)*W_pad/32)
+    const int bph = sh.W_pad >> 5;
+    float v = 0.f;
+    for (int w = 0; w < kF1Waves; ++w)
+      for (int k = 0; k < bph; ++k) v += lds_cross[w][threadIdx.x * bph + k];
+    c.cross_part[(long long)(l * sh.Hq + gkv * sh.G + threadIdx.x) * sh.tiles_score + b] = v;
+  }
+
+  // top-B split on the importances still in LDS
+  int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  int *assign = c.assign + unit * sh.T + s.tok_off;
+  select_top_b<kF1Threads>(lds_keys, L, sh.W, s.B, kept, assign, scratch);
+}
+
+// ============================ flow + match ==================================================
+constexpr int kF2Threads = 256;
+constexpr int kF2Waves = kF2Threads / 64;
+
+template <int D>
+__global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad) {
+  using CF = Cfg<kBF16, D>;
+  constexpr int NCH = CF::NCH, NF = CF::NF;
+  extern __shared__ __align__(16) uint4 lds_dyn[];
+  uint4 *lds_piv = lds_dyn;                                                  // [b_pad][NCH+1]
+  float *lds_w = reinterpret_cast<float *>(lds_piv + b_pad * (NCH + 1));     // [b_pad]
+  float *lds_bias = lds_w + b_pad;                                           // [2][b_pad]
+  float *lds_head = lds_bias + 2 * b_pad;                                    // [Hq]
+  __shared__ float sh_rho;
+  __shared__ int sh_dropped;
+
+  const Shape &sh = c.sh;
+  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const SeqInfo s = load_seq(c.meta, b);
+  const int L = s.L;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+  const long long unit = (long long)l * sh.Hkv + gkv;
+
+  // flow: every workgroup of the layer folds the same numbers in the same order
+  for (int h = threadIdx.x; h < sh.Hq; h += kF2Threads)
+    lds_head[h] = c.cross_part[(long long)(l * sh.Hq + h) * sh.tiles_score + b] / (float)sh.W;
+  if (threadIdx.x == 0) sh_dropped = 0;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float acc = 0.f;
+    for (int h = 0; h < sh.Hq; ++h) acc += lds_head[h];
+    const float rho = acc / (float)sh.Hq;
+    sh_rho = rho;
+    if (gkv == 0) {
+      c.rho[l * sh.batch + b] = rho;
+      c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  const bool mode_cross = sh_rho > sh.theta;
+
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
+                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  const uint8_t *mod = c.mod + s.tok_off;
+  const float *imp = c.importance + unit * sh.T + s.tok_off;
+  const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  int *assign = c.assign + unit * sh.T + s.tok_off;
+
+  // first token tile of this wave is requested before the pivots are staged
+  const int ntiles = (L + 31) >> 5;
+  uint4 kf[NF];
+  int t = wave;
+  if (t < ntiles) {
+    const uint4 *row = K + (long long)min(t * 32 + n, L - 1) * sh.ks_tok + half;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
+  }
+
+  // stage all pivots once: rows, inverse norms, eligibility per token modality
+  constexpr int kRowsPerPass = kF2Threads / NCH;
+  for (int r0 = 0; r0 < b_pad; r0 += kRowsPerPass) {
+    const int pr = r0 + threadIdx.x / NCH, ch = threadIdx.x % NCH;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    int ptok = 0;
+    const bool real = pr < s.B;
+    if (real) {
+      ptok = kept[pr];
+      v = K[(long long)ptok * sh.ks_tok + ch];
+    }
+    if (pr < b_pad) lds_piv[pr * (NCH + 1) + ch] = v;
+    float ss = chunk_sumsq<kBF16>(v);
+#pragma unroll
+    for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if (ch == 0 && pr < b_pad) {
+      const bool ok = real && !(imp[ptok] > s.tau);
+      const int pm = real ? mod[ptok] : 0;
+      lds_w[pr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+      lds_bias[pr] = ok && (mode_cross || pm == 0) ? 0.f : -INFINITY;
+      lds_bias[b_pad + pr] = ok && (mode_cross || pm == 1) ? 0.f : -INFINITY;
+    }
+  }
+  __syncthreads();
+
+  const int nblk = b_pad >> 5;
+  int dropped = 0;
+  for (; t < ntiles; t += kF2Waves) {
+    const int tok = t * 32 + n;
+    const int tc = min(tok, L - 1);
+    const int cur = assign[tc];
+    const float *bias = lds_bias + (mod[tc] ? b_pad : 0);
+    uint4 nxt[NF];
+    if (t + kF2Waves < ntiles) {
+      const uint4 *row = K + (long long)min((t + kF2Waves) * 32 + n, L - 1) * sh.ks_tok + half;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) nxt[f] = row[2 * f];
+    }
+    float best = -INFINITY;
+    int best_slot = -1;
+    for (int pb = 0; pb < nblk; ++pb) {
+      f32x16_t acc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+      const uint4 *prow = lds_piv + (pb * 32 + n) * (NCH + 1) + half;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) mma_chunk<kBF16>(acc, prow[2 * f], kf[f]);  // [pivot][token]
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int pr = pb * 32 + acc_row(i, half);
+        const float u = fmaf(acc[i], lds_w[pr], bias[pr]);
+        if (u > best) { best = u; best_slot = pr; }
+      }
+    }
+    const float ob = __shfl_xor(best, 32, 64);
+    const int os = __shfl_xor(best_slot, 32, 64);
+    if (ob > best || (ob == best && (unsigned)os < (unsigned)best_slot)) { best = ob; best_slot = os; }
+    if (half == 0 && tok < L && cur == -2) {
+      assign[tok] = best_slot;
+      dropped += best_slot < 0;
+    }
+    if (t + kF2Waves < ntiles) {
+#pragma unroll
+      for (int f = 0; f < NF; ++f) kf[f] = nxt[f];
+    }
+  }
+  dropped = wave_sum_int(dropped);
+  if (lane == 0 && dropped) atomicAdd(&sh_dropped, dropped);
+  __syncthreads();
+  if (threadIdx.x == 0) c.n_dropped[unit * sh.batch + b] = sh_dropped;
+}
+
+// ============================ merge =========================================================
+constexpr int kF3Threads = 1024;
+constexpr int kF3Waves = kF3Threads / 64;
+
+struct MergeLds {  // element offsets (ints) into the dynamic LDS block
+  int tbl, seg, members, tasks, multi, partials, total_bytes;
+};
+
+__host__ __device__ inline MergeLds merge_lds_layout(int maxB, int maxE, int d) {
+  MergeLds m;
+  int off = 0;
+  m.tbl = off; off += maxB * kF3Waves;
+  m.seg = off; off += maxB + 1;
+  m.members = off; off += maxE + 1;
+  off = (off + 3) & ~3;
+  m.tasks = off; off += 4 * (maxB + maxE / kTaskChunk + 1);
+  m.multi = off; off += 4 * (maxE / (kTaskChunk + 1) + 1);
+  m.partials = off; off += (2 * (maxE / kTaskChunk) + 2) * 2 * d;
+  m.total_bytes = off * 4;
+  return m;
+}
+
+__device__ __forceinline__ unsigned long long same_slot_lanes(bool member, int slot, int nbits) {
+  unsigned long long m = __ballot(member);
+  for (int bit = 0; bit < nbits; ++bit) {
+    const bool one = (slot >> bit) & 1;
+    const unsigned long long bb = __ballot(member && one);
+    m &= one ? bb : ~bb;
+  }
+  return m;
+}
+
+template <int D>
+__global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB, int maxE) {
+  using CF = Cfg<kBF16, D>;
+  constexpr int LPR = CF::NCH, RPL = 64 / LPR, EPC = CF::kElemsPerChunk, U = 4;
+  extern __shared__ __align__(16) int lds_i[];
+  __shared__ int lds_wave[kF3Waves + 1];
+  __shared__ int sh_counts[2];  // tasks, multi-task slots
+  const MergeLds lay = merge_lds_layout(maxB, maxE, D);
+  int *tbl = lds_i + lay.tbl;
+  int *seg = lds_i + lay.seg;
+  int *members = lds_i + lay.members;
+  int4 *tasks = reinterpret_cast<int4 *>(lds_i + lay.tasks);
+  int4 *multi = reinterpret_cast<int4 *>(lds_i + lay.multi);
+  float *partials = reinterpret_cast<float *>(lds_i + lay.partials);
+
+  const Shape &sh = c.sh;
+  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const SeqInfo s = load_seq(c.meta, b);
+  const long long unit = (long long)l * sh.Hkv + gkv;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int *assign = c.assign + unit * sh.T + s.tok_off;
+  const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  constexpr int NW = kF3Waves;
+
+  int nbits = 0;
+  while ((1 << nbits) < s.B) ++nbits;
+  const int range = ((s.L + NW - 1) / NW + 63) & ~63;
+  const int r0 = wave * range, r1 = min(s.L, r0 + range);
+
+  for (int i = threadIdx.x; i < s.B * NW; i += kF3Threads) tbl[i] = 0;
+  __syncthreads();
+  // members of each slot inside each wave's token range (this wave's tokens stay in registers)
+  // range <= 64 * ceil(L / 1024) = 64 for L <= 1024: one chunk per wave
+  for (int i0 = r0; i0 < r1; i0 += 64) {
+    const int i = i0 + lane;
+    const int slot = i < r1 ? assign[i] : -1;
+    const bool member = slot >= 0 && kept[slot] != i;
+    const unsigned long long m = same_slot_lanes(member, slot, nbits);
+    if (member && (m & ((1ull << lane) - 1)) == 0) tbl[slot * NW + wave] += __popcll(m);
+  }
+  __syncthreads();
+  {  // scan over slots (B <= 256 < threads: one round)
+    const int slot = threadIdx.x;
+    int n = 0;
+    if (slot < s.B)
+      for (int w = 0; w < NW; ++w) n += tbl[slot * NW + w];
+    const int nt = slot < s.B ? max(1, (n + kTaskChunk - 1) / kTaskChunk) : 0;
+    const int is_multi = nt > 1;
+    int tot_n, tot_t, tot_m, tot_p;
+    const int sg = block_exclusive_scan<kF3Threads>(n, lds_wave, &tot_n);
+    const int tb = block_exclusive_scan<kF3Threads>(nt, lds_wave, &tot_t);
+    const int mb = block_exclusive_scan<kF3Threads>(is_multi, lds_wave, &tot_m);
+    const int pb = block_exclusive_scan<kF3Threads>(is_multi ? nt : 0, lds_wave, &tot_p);
+    if (slot < s.B) {
+      seg[slot] = sg;
+      int base = sg;
+      for (int w = 0; w < NW; ++w) {
+        const int t = tbl[slot * NW + w];
+        tbl[slot * NW + w] = base;
+        base += t;
+      }
+      for (int j = 0; j < nt; ++j)
+        tasks[tb + j] = make_int4(slot, sg + j * kTaskChunk, min(kTaskChunk, n - j * kTaskChunk),
+                                  is_multi ? pb + j : -1);
+      if (is_multi) multi[mb] = make_int4(slot, pb, nt, n);
+    }
+    if (threadIdx.x == 0) { sh_counts[0] = tot_t; sh_counts[1] = tot_m; }
+  }
+  __syncthreads();
+  for (int i0 = r0; i0 < r1; i0 += 64) {
+    const int i = i0 + lane;
+    const int slot = i < r1 ? assign[i] : -1;
+    const bool member = slot >= 0 && kept[slot] != i;
+    const unsigned long long m = same_slot_lanes(member, slot, nbits);
+    const unsigned long long below = m & ((1ull << lane) - 1);
+    if (member) {
+      const int cur = tbl[slot * NW + wave];
+      members[cur + __popcll(below)] = i;
+      if (below == 0) tbl[slot * NW + wave] = cur + __popcll(m);
+    }
+  }
+  __syncthreads();
+
+  // segment sums: one wave per task, 64/LPR rows per load, U loads in flight
+  const int n_tasks = sh_counts[0], n_multi = sh_counts[1];
+  const int rg = lane / LPR, ch = lane % LPR;
+  const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + head_off;
+  const uint4 *V = reinterpret_cast<const uint4 *>(c.V) + head_off;
+  uint4 *Ko = reinterpret_cast<uint4 *>(c.K_out) + (unit * sh.SB + s.kept_off) * LPR;
+  uint4 *Vo = reinterpret_cast<uint4 *>(c.V_out) + (unit * sh.SB + s.kept_off) * LPR;
+  for (int q = wave; q < n_tasks; q += kF3Waves) {
+    const int4 task = tasks[q];
+    const int *mem = members + task.y;
+    float ak[EPC], av[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
+    const bool single = task.w < 0;
+    if (single && rg == 0) {
+      const int pivot_tok = kept[task.x];
+      chunk_to_floats<kBF16>(K[(long long)pivot_tok * sh.ks_tok + ch], ak);
+      chunk_to_floats<kBF16>(V[(long long)pivot_tok * sh.ks_tok + ch], av);
+    }
+    for (int j0 = rg; j0 < task.z; j0 += RPL * U) {
+      int tokv[U];
+      uint4 kc[U], vc[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = j0 + u * RPL;
+        tokv[u] = j < task.z ? mem[j] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (tokv[u] >= 0) {
+          kc[u] = K[(long long)tokv[u] * sh.ks_tok + ch];
+          vc[u] = V[(long long)tokv[u] * sh.ks_tok + ch];
+        }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (tokv[u] >= 0) {
+          float fk[EPC], fv[EPC];
+          chunk_to_floats<kBF16>(kc[u], fk);
+          chunk_to_floats<kBF16>(vc[u], fv);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
+        }
+    }
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        ak[e] += __shfl_xor(ak[e], o, 64);
+        av[e] += __shfl_xor(av[e], o, 64);
+      }
+    if (rg == 0) {
+      if (single) {
+        const float den = (float)(1 + task.z);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) { ak[e] = ak[e] / den; av[e] = av[e] / den; }
+        Ko[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(ak);
+        Vo[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(av);
+      } else {
+        float *p = partials + (long long)task.w * 2 * D + ch * EPC;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) { p[e] = ak[e]; p[D + e] = av[e]; }
+      }
+    }
+  }
+  __syncthreads();
+  // slots cut into several tasks: pivot row plus the partials in task order
+  for (int q = wave; q < n_multi; q += kF3Waves) {
+    const int4 e4 = multi[q];  // (slot, first partial, partials, members)
+    const int pivot_tok = kept[e4.x];
+    const float den = (float)(1 + e4.w);
+    if (lane < 2 * LPR) {
+      const int tensor = lane / LPR, cch = lane % LPR;
+      const uint4 *src = tensor ? V : K;
+      float acc[EPC];
+      chunk_to_floats<kBF16>(src[(long long)pivot_tok * sh.ks_tok + cch], acc);
+      for (int p = 0; p < e4.z; ++p) {
+        const float *pp = partials + (long long)(e4.y + p) * 2 * D + tensor * D + cch * EPC;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] += pp[e];
+      }
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] = acc[e] / den;
+      (tensor ? Vo : Ko)[(long long)e4.x * LPR + cch] = floats_to_chunk<kBF16>(acc);
+    }
+  }
+}
+
+// ---- dispatch --------------------------------------------------------------------------------
+template <int D, int RB>
+hipError_t launch_f1(const Ctx &c, int nt) {
+  const dim3 grid(c.sh.batch, c.sh.Hkv, c.sh.n_layers);
+  ProfScope ps(c.stream, KID_UNIT_SCORE_SELECT);
+  switch (nt) {
+    case 1: unit_score_select_kernel<D, RB, 1><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    case 2: unit_score_select_kernel<D, RB, 2><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    case 3: unit_score_select_kernel<D, RB, 3><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    default: unit_score_select_kernel<D, RB, 4><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+  }
+  return hipGetLastError();
+}
+
+size_t match_lds_bytes(const Shape &sh, int b_pad) {
+  const int nch = sh.d * 2 / 16;
+  return (size_t)b_pad * (nch + 1) * 16 + (size_t)b_pad * 3 * 4 + (size_t)sh.Hq * 4;
+}
+
+template <int D>
+hipError_t launch_f2(const Ctx &c) {
+  const int b_pad = (c.sh.maxB + 31) / 32 * 32;
+  const size_t lds = match_lds_bytes(c.sh, b_pad);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_match_kernel<D>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  ProfScope ps(c.stream, KID_UNIT_MATCH);
+  unit_match_kernel<D><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kF2Threads, lds, c.stream>>>(c, b_pad);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_f3(const Ctx &c) {
+  const MergeLds lay = merge_lds_layout(c.sh.maxB, c.sh.maxE, D);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_merge_kernel<D>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lay.total_bytes);
+  if (e != hipSuccess) return e;
+  ProfScope ps(c.stream, KID_UNIT_MERGE);
+  unit_merge_kernel<D><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kF3Threads, lay.total_bytes, c.stream>>>(
+      c, c.sh.maxB, c.sh.maxE);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool unit_path_fits(const Shape &sh) {
+  if (!sh.bf16 || sh.maxL > 1024 || sh.R_pad > 64 || sh.maxB > 256 || sh.Hq > 4096) return false;
+  const int b_pad = (sh.maxB + 31) / 32 * 32;
+  if (match_lds_bytes(sh, b_pad) > 150 * 1024) return false;
+  if ((size_t)merge_lds_layout(sh.maxB, sh.maxE, sh.d).total_bytes > 150 * 1024) return false;
+  return true;
+}
+
+hipError_t launch_unit_plan(const Ctx &c) {
+  const int nt = ((c.sh.maxL + 31) / 32 + kF1Waves - 1) / kF1Waves;
+  const int rb = c.sh.R_pad / 32;
+  hipError_t e;
+  if (c.sh.d == 128) e = rb == 1 ? launch_f1<128, 1>(c, nt) : launch_f1<128, 2>(c, nt);
+  else e = rb == 1 ? launch_f1<64, 1>(c, nt) : launch_f1<64, 2>(c, nt);
+  if (e != hipSuccess) return e;
+  return c.sh.d == 128 ? launch_f2<128>(c) : launch_f2<64>(c);
+}
+
+hipError_t launch_unit_merge(const Ctx &c) { return c.sh.d == 128 ? launch_f3<128>(c) : launch_f3<64>(c); }
+
+}  // namespace flowmm

@@ -19,11 +19,11 @@ def upload(wl, device="cuda:0", layers=None):
     return fb.upload_workload(wl, device, layers)
 
 
-def run_gpu(wl, theta=None, tau=None, device="cuda:0", tensors=None):
+def run_gpu(wl, theta=None, tau=None, device="cuda:0", tensors=None, flags=0):
     """Run flowmm_plan + flowmm_merge through the C ABI; returns numpy copies of everything."""
     import torch
     from paper_2511_05534_amd import binding as fb
-    params = fb.Params.from_workload(wl, theta=theta, tau=tau)
+    params = fb.Params.from_workload(wl, theta=theta, tau=tau, flags=flags)
     K, V, Q = tensors if tensors is not None else upload(wl, device)
     bufs = fb.DeviceBuffers(params, device)
     stream = torch.cuda.current_stream().cuda_stream

@@ -26,7 +26,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(fb.flowmm_span) == 12
     assert C.sizeof(fb.flowmm_plan_buffers) == 48
     # int32 x6, 4 pointers, int32 + 2 floats (+pad), pointer, 6 int64
-    assert C.sizeof(fb.flowmm_params) == 24 + 32 + 16 + 8 + 48
+    assert C.sizeof(fb.flowmm_params) == 24 + 32 + 16 + 8 + 48 + 8
 
 
 def params_for(**kw):
@@ -67,6 +67,7 @@ BAD = [
     (dict(k_strides=(2 * 500 * 128, 500 * 128, 132)), fb.FLOWMM_EINVAL, "16 bytes"),
     (dict(n_q_heads=64, n_kv_heads=1, window=128, budgets=[130, 140]), fb.FLOWMM_EUNSUPPORTED, "LDS"),
     (dict(seqlens=[300, 0], budgets=[30, 0]), fb.FLOWMM_EINVAL, "increasing"),
+    (dict(flags=2), fb.FLOWMM_EINVAL, "flags"),
 ]
 
 

@@ -40,14 +40,38 @@ SMALL_CASES = {
 }
 
 
+@pytest.mark.parametrize("path", ["auto", "generic"])
 @pytest.mark.parametrize("name", list(SMALL_CASES))
-def test_small_cases_match_oracle(oracle, name):
+def test_small_cases_match_oracle(oracle, name, path):
+    """`auto` lets the library pick (short bf16 prompts take the unit-resident kernels); `generic`
+    forces the multi-workgroup kernels on the same inputs."""
     w = small(name, **SMALL_CASES[name])
-    print(f"case {name}: L={w.seqlens} B={w.budgets} dtype={w.dtype}", flush=True)
-    gpu = run_gpu(w)
+    print(f"case {name} [{path}]: L={w.seqlens} B={w.budgets} dtype={w.dtype}", flush=True)
+    gpu = run_gpu(w, flags=0 if path == "auto" else 1)
     rep = Report()
     for l in range(w.n_layers):
         check_layer(oracle, w, gpu, l, report=rep)
+    print(rep, flush=True)
+
+
+def test_both_paths_agree_on_decisions():
+    """Same kept sets and assignments from the unit-resident and the generic kernels (decisions are
+    taken on fp32 numbers that may differ in the last bits, so compare where they are equal)."""
+    w = small("paths", Hq=2, Hkv=2, spans=((35, 576, 64),), pct=(10,), n_layers=3)
+    a = run_gpu(w, flags=0)
+    b = run_gpu(w, flags=1)
+    same_I = (a["importance"] == b["importance"]).mean()
+    print(f"identical importances: {same_I:.4f}", flush=True)
+    assert np.allclose(a["importance"], b["importance"], rtol=1e-5, atol=0)
+    agree = (a["assign"] == b["assign"]).mean()
+    assert agree > 0.995, agree
+    assert (a["mode"] == b["mode"]).all()
+
+
+def test_config1_generic_path_sampled(oracle):
+    w = wl.config(1, n_layers=2)
+    gpu = run_gpu(w, flags=1)
+    rep = check_layer(oracle, w, gpu, 1, kv_heads=[3, 30])
     print(rep, flush=True)
 
 
@@ -130,7 +154,7 @@ def test_ragged_batch_equals_each_sequence_alone():
 
 
 @pytest.mark.parametrize("cfg,n_layers,sample", [
-    (1, 32, [(0, [0, 17]), (31, [5])]),      # the benchmark configuration, full depth
+    (1, 32, [(0, [0, 17]), (31, [5])]),      # the benchmark configuration, full depth (unit-resident kernels)
     (2, 2, [(1, [0, 3])]),
     (3, 2, [(0, [2])]),
     (4, 2, [(1, [1])]),
