@@ -15,26 +15,27 @@ struct SelectScratch {
   int remaining;
 };
 
-// exclusive prefix sum over the workgroup, in thread order; *total receives the block sum
-template <int THREADS>
-__device__ __forceinline__ int block_exclusive_scan(int v, int *lds_wave /*[THREADS/64+1]*/, int *total) {
+// exclusive prefix sum over the workgroup, in thread order; *total receives the block sum.
+// T is int or long long (several small counters packed into one word scan together).
+template <int THREADS, typename T>
+__device__ __forceinline__ T block_exclusive_scan(T v, T *lds_wave /*[THREADS/64+1]*/, T *total) {
   constexpr int kWaves = THREADS / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
+  T inc = v;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const int u = __shfl_up(inc, o, 64);
+    const T u = __shfl_up(inc, o, 64);
     if (lane >= o) inc += u;
   }
   __syncthreads();  // lds_wave may still be read from a previous call
   if (lane == 63) lds_wave[wave] = inc;
   __syncthreads();
   if (wave == 0) {
-    const int w = lane < kWaves ? lds_wave[lane] : 0;
-    int winc = w;
+    const T w = lane < kWaves ? lds_wave[lane] : (T)0;
+    T winc = w;
 #pragma unroll
     for (int o = 1; o < kWaves; o <<= 1) {
-      const int u = __shfl_up(winc, o, 64);
+      const T u = __shfl_up(winc, o, 64);
       if (lane >= o) winc += u;
     }
     if (lane < kWaves) lds_wave[lane] = winc - w;
@@ -84,7 +85,7 @@ __device__ __forceinline__ void select_top_b(const unsigned *keys, int L, int W,
       // bins in descending order: thread t looks at bin 255 - t
       const int cnt = threadIdx.x < 256 ? sc.hist[255 - threadIdx.x] : 0;
       int total;
-      const int before = block_exclusive_scan<THREADS>(cnt, sc.wave_sums, &total);
+      const int before = block_exclusive_scan<THREADS, int>(cnt, sc.wave_sums, &total);
       if (threadIdx.x < 256 && before < remaining && remaining <= before + cnt) {
         sc.prefix = prefix | ((unsigned)(255 - threadIdx.x) << shift);
         sc.remaining = remaining - before;
@@ -112,7 +113,7 @@ __device__ __forceinline__ void select_top_b(const unsigned *keys, int L, int W,
       }
     }
     int total;
-    const int before = block_exclusive_scan<THREADS>(gt | (eq << 16), sc.wave_sums, &total);
+    const int before = block_exclusive_scan<THREADS, int>(gt | (eq << 16), sc.wave_sums, &total);
     const int gt_before = gt_carry + (before & 0xffff);
     const int eq_before = eq_carry + (before >> 16);
     if (i < L) {

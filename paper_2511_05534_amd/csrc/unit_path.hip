@@ -19,6 +19,19 @@ namespace {
 
 constexpr bool kBF16 = true;
 
+// Build with -DFLOWMM_TRACE to make thread 0 of every workgroup stamp the 100 MHz wall clock at
+// the phase boundaries below into a buffer set through flowmm_trace_set (kernel tuning only).
+#ifdef FLOWMM_TRACE
+static __device__ unsigned long long *g_trace;
+#define TRACE(k)                                                                                          \
+  do {                                                                                                    \
+    if (threadIdx.x == 0)                                                                                 \
+      g_trace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (k)] = wall_clock64(); \
+  } while (0)
+#else
+#define TRACE(k)
+#endif
+
 // ============================ score + select ================================================
 constexpr int kF1Threads = 512;
 constexpr int kF1Waves = kF1Threads / 64;
@@ -39,6 +52,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
 
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  TRACE(0);
   const SeqInfo s = load_seq(c.meta, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
@@ -61,6 +75,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
     }
   }
   __syncthreads();
+  TRACE(1);
 
   // logits of this wave's key tiles: wave w owns tiles w, w+8, ... (32 keys each)
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
@@ -90,6 +105,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
     }
   }
 
+  TRACE(2);
   // mask, move to the log2 domain, per-row maximum over this wave's keys
   const float cl = sh.scale_log2e;
   float rowv[RB][16];
@@ -158,6 +174,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
   }
   __syncthreads();
 
+  TRACE(3);
   // probabilities reduced over the query rows: importance per key, cross-modal mass per head
   const float inv_rows = 1.0f / (float)(sh.G * sh.W);
   float *imp = c.importance + unit * sh.T + s.tok_off;
@@ -209,10 +226,12 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
     c.cross_part[(long long)(l * sh.Hq + gkv * sh.G + threadIdx.x) * sh.tiles_score + b] = v;
   }
 
+  TRACE(4);
   // top-B split on the importances still in LDS
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
   select_top_b<kF1Threads>(lds_keys, L, sh.W, s.B, kept, assign, scratch);
+  TRACE(5);
 }
 
 // ============================ flow + match ==================================================
@@ -238,6 +257,7 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const long long unit = (long long)l * sh.Hkv + gkv;
 
+  TRACE(8);
   // flow: every workgroup of the layer folds the same numbers in the same order
   for (int h = threadIdx.x; h < sh.Hq; h += kF2Threads)
     lds_head[h] = c.cross_part[(long long)(l * sh.Hq + h) * sh.tiles_score + b] / (float)sh.W;
@@ -263,6 +283,7 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
 
+  TRACE(9);
   // first token tile of this wave is requested before the pivots are staged
   const int ntiles = (L + 31) >> 5;
   uint4 kf[NF];
@@ -298,6 +319,7 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   }
   __syncthreads();
 
+  TRACE(10);
   const int nblk = b_pad >> 5;
   int dropped = 0;
   for (; t < ntiles; t += kF2Waves) {
@@ -339,30 +361,35 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
       for (int f = 0; f < NF; ++f) kf[f] = nxt[f];
     }
   }
+  TRACE(11);
   dropped = wave_sum_int(dropped);
   if (lane == 0 && dropped) atomicAdd(&sh_dropped, dropped);
   __syncthreads();
+  TRACE(12);
   if (threadIdx.x == 0) c.n_dropped[unit * sh.batch + b] = sh_dropped;
 }
 
 // ============================ merge =========================================================
-constexpr int kF3Threads = 1024;
+constexpr int kF3Threads = 256;
 constexpr int kF3Waves = kF3Threads / 64;
+constexpr int kF3Chunks = 4;   // 64-token chunks a wave walks: ceil(1024 / 4 waves / 64)
+constexpr int kUnitChunk = 64;  // members per task of a slot that is cut up (keeps the partial sums in LDS few)
 
 struct MergeLds {  // element offsets (ints) into the dynamic LDS block
-  int tbl, seg, members, tasks, multi, partials, total_bytes;
+  int tbl, kept, copies, members, tasks, multi, partials, total_bytes;
 };
 
 __host__ __device__ inline MergeLds merge_lds_layout(int maxB, int maxE, int d) {
   MergeLds m;
   int off = 0;
   m.tbl = off; off += maxB * kF3Waves;
-  m.seg = off; off += maxB + 1;
+  m.kept = off; off += maxB;
+  m.copies = off; off += maxB;
   m.members = off; off += maxE + 1;
   off = (off + 3) & ~3;
-  m.tasks = off; off += 4 * (maxB + maxE / kTaskChunk + 1);
-  m.multi = off; off += 4 * (maxE / (kTaskChunk + 1) + 1);
-  m.partials = off; off += (2 * (maxE / kTaskChunk) + 2) * 2 * d;
+  m.tasks = off; off += 4 * (maxB + maxE / kUnitChunk + 1);
+  m.multi = off; off += 4 * (maxE / (kUnitChunk + 1) + 1);
+  m.partials = off; off += (2 * (maxE / kUnitChunk) + 2) * 2 * d;
   m.total_bytes = off * 4;
   return m;
 }
@@ -377,19 +404,26 @@ __device__ __forceinline__ unsigned long long same_slot_lanes(bool member, int s
   return m;
 }
 
+// One workgroup per unit.  A stable counting sort groups the evicted tokens by slot in LDS; then
+// every group of LPR lanes (one 16-byte chunk per lane, so a group covers one row per load)
+// works on its own: pivots nobody merges into are copied, U rows in flight per group; the other
+// slots become tasks (a slot, or a chunk of at most kUnitChunk members of a larger slot) that a
+// group adds up row after row, U row loads in flight, large chunks first; slots cut into several
+// tasks are folded from their partial sums at the end.
 template <int D>
 __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB, int maxE) {
   using CF = Cfg<kBF16, D>;
-  constexpr int LPR = CF::NCH, RPL = 64 / LPR, EPC = CF::kElemsPerChunk, U = 4;
+  constexpr int LPR = CF::NCH, RPL = 64 / LPR, EPC = CF::kElemsPerChunk, U = 8;
   extern __shared__ __align__(16) int lds_i[];
-  __shared__ int lds_wave[kF3Waves + 1];
-  __shared__ int sh_counts[2];  // tasks, multi-task slots
+  __shared__ long long lds_wave[kF3Waves + 1];
+  __shared__ int sh_next;  // next task nobody has taken yet
   const MergeLds lay = merge_lds_layout(maxB, maxE, D);
-  int *tbl = lds_i + lay.tbl;
-  int *seg = lds_i + lay.seg;
-  int *members = lds_i + lay.members;
-  int4 *tasks = reinterpret_cast<int4 *>(lds_i + lay.tasks);
-  int4 *multi = reinterpret_cast<int4 *>(lds_i + lay.multi);
+  int *tbl = lds_i + lay.tbl;          // [B][waves] members per wave range, later write cursors
+  int *lds_kept = lds_i + lay.kept;    // [B] pivot positions
+  int *copies = lds_i + lay.copies;    // slots without members
+  int *members = lds_i + lay.members;  // evicted tokens grouped by slot, ascending
+  int4 *tasks = reinterpret_cast<int4 *>(lds_i + lay.tasks);  // (slot, first member, members, partial or -1)
+  int4 *multi = reinterpret_cast<int4 *>(lds_i + lay.multi);  // (slot, first partial, partials, members)
   float *partials = reinterpret_cast<float *>(lds_i + lay.partials);
 
   const Shape &sh = c.sh;
@@ -401,92 +435,135 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
   const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   constexpr int NW = kF3Waves;
 
+  TRACE(0);
   int nbits = 0;
   while ((1 << nbits) < s.B) ++nbits;
-  const int range = ((s.L + NW - 1) / NW + 63) & ~63;
+  const int range = ((s.L + NW - 1) / NW + 63) & ~63;  // <= 64 * kF3Chunks since L <= 1024
   const int r0 = wave * range, r1 = min(s.L, r0 + range);
 
+  // this wave's assignments and the pivot list arrive in one round trip
+  int slot_of[kF3Chunks];
+#pragma unroll
+  for (int k = 0; k < kF3Chunks; ++k) {
+    const int i = r0 + k * 64 + lane;
+    slot_of[k] = i < r1 ? assign[i] : -1;
+  }
+  for (int i = threadIdx.x; i < s.B; i += kF3Threads) lds_kept[i] = kept[i];
   for (int i = threadIdx.x; i < s.B * NW; i += kF3Threads) tbl[i] = 0;
+  if (threadIdx.x == 0) sh_next = kF3Waves * (64 / CF::NCH);  // the first tasks go to the groups in order
   __syncthreads();
-  // members of each slot inside each wave's token range (this wave's tokens stay in registers)
-  // range <= 64 * ceil(L / 1024) = 64 for L <= 1024: one chunk per wave
-  for (int i0 = r0; i0 < r1; i0 += 64) {
-    const int i = i0 + lane;
-    const int slot = i < r1 ? assign[i] : -1;
-    const bool member = slot >= 0 && kept[slot] != i;
-    const unsigned long long m = same_slot_lanes(member, slot, nbits);
-    if (member && (m & ((1ull << lane) - 1)) == 0) tbl[slot * NW + wave] += __popcll(m);
+  // members of each slot inside each wave's token range
+  unsigned long long same[kF3Chunks];
+  bool member[kF3Chunks];
+#pragma unroll
+  for (int k = 0; k < kF3Chunks; ++k) {
+    const int i = r0 + k * 64 + lane;
+    member[k] = slot_of[k] >= 0 && lds_kept[slot_of[k]] != i;
+    same[k] = same_slot_lanes(member[k], slot_of[k], nbits);
+    if (member[k] && (same[k] & ((1ull << lane) - 1)) == 0) tbl[slot_of[k] * NW + wave] += __popcll(same[k]);
   }
   __syncthreads();
-  {  // scan over slots (B <= 256 < threads: one round)
+  TRACE(1);
+  int n_tasks, n_multi, n_copy;
+  {  // one packed scan over the slots (B <= 256 <= threads): member offsets, multi-task slots,
+     // their chunks, single-task slots and copy-only slots
     const int slot = threadIdx.x;
     int n = 0;
     if (slot < s.B)
       for (int w = 0; w < NW; ++w) n += tbl[slot * NW + w];
-    const int nt = slot < s.B ? max(1, (n + kTaskChunk - 1) / kTaskChunk) : 0;
-    const int is_multi = nt > 1;
-    int tot_n, tot_t, tot_m, tot_p;
-    const int sg = block_exclusive_scan<kF3Threads>(n, lds_wave, &tot_n);
-    const int tb = block_exclusive_scan<kF3Threads>(nt, lds_wave, &tot_t);
-    const int mb = block_exclusive_scan<kF3Threads>(is_multi, lds_wave, &tot_m);
-    const int pb = block_exclusive_scan<kF3Threads>(is_multi ? nt : 0, lds_wave, &tot_p);
-    if (slot < s.B) {
-      seg[slot] = sg;
+    const int nt = (n + kUnitChunk - 1) / kUnitChunk;  // 0: copy, 1: one task, more: chunks + fold
+    const bool valid = slot < s.B;
+    const long long packed = (long long)n | ((long long)(valid && nt > 1) << 16) |
+                             ((long long)(nt > 1 ? nt : 0) << 24) | ((long long)(valid && nt == 1) << 36) |
+                             ((long long)(valid && nt == 0) << 48);
+    long long tot;
+    const long long ex = block_exclusive_scan<kF3Threads, long long>(packed, lds_wave, &tot);
+    const int sg = (int)(ex & 0xffff), mb = (int)((ex >> 16) & 0xff), pb = (int)((ex >> 24) & 0xfff),
+              sb = (int)((ex >> 36) & 0xfff), cb = (int)((ex >> 48) & 0xfff);
+    const int n_part = (int)((tot >> 24) & 0xfff);
+    n_multi = (int)((tot >> 16) & 0xff);
+    n_tasks = n_part + (int)((tot >> 36) & 0xfff);
+    n_copy = (int)((tot >> 48) & 0xfff);
+    if (valid) {
       int base = sg;
       for (int w = 0; w < NW; ++w) {
         const int t = tbl[slot * NW + w];
         tbl[slot * NW + w] = base;
         base += t;
       }
-      for (int j = 0; j < nt; ++j)
-        tasks[tb + j] = make_int4(slot, sg + j * kTaskChunk, min(kTaskChunk, n - j * kTaskChunk),
-                                  is_multi ? pb + j : -1);
-      if (is_multi) multi[mb] = make_int4(slot, pb, nt, n);
-    }
-    if (threadIdx.x == 0) { sh_counts[0] = tot_t; sh_counts[1] = tot_m; }
-  }
-  __syncthreads();
-  for (int i0 = r0; i0 < r1; i0 += 64) {
-    const int i = i0 + lane;
-    const int slot = i < r1 ? assign[i] : -1;
-    const bool member = slot >= 0 && kept[slot] != i;
-    const unsigned long long m = same_slot_lanes(member, slot, nbits);
-    const unsigned long long below = m & ((1ull << lane) - 1);
-    if (member) {
-      const int cur = tbl[slot * NW + wave];
-      members[cur + __popcll(below)] = i;
-      if (below == 0) tbl[slot * NW + wave] = cur + __popcll(m);
+      if (nt == 0) {
+        copies[cb] = slot;
+      } else if (nt == 1) {
+        tasks[n_part + sb] = make_int4(slot, sg, n, -1);  // after all the chunks of large slots
+      } else {
+        for (int j = 0; j < nt; ++j)
+          tasks[pb + j] = make_int4(slot, sg + j * kUnitChunk, min(kUnitChunk, n - j * kUnitChunk), pb + j);
+        multi[mb] = make_int4(slot, pb, nt, n);
+      }
     }
   }
   __syncthreads();
+  TRACE(2);
+#pragma unroll
+  for (int k = 0; k < kF3Chunks; ++k) {
+    const unsigned long long below = same[k] & ((1ull << lane) - 1);
+    if (member[k]) {
+      const int cur = tbl[slot_of[k] * NW + wave];
+      members[cur + __popcll(below)] = r0 + k * 64 + lane;
+      if (below == 0) tbl[slot_of[k] * NW + wave] = cur + __popcll(same[k]);
+    }
+  }
 
-  // segment sums: one wave per task, 64/LPR rows per load, U loads in flight
-  const int n_tasks = sh_counts[0], n_multi = sh_counts[1];
   const int rg = lane / LPR, ch = lane % LPR;
   const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + head_off;
   const uint4 *V = reinterpret_cast<const uint4 *>(c.V) + head_off;
   uint4 *Ko = reinterpret_cast<uint4 *>(c.K_out) + (unit * sh.SB + s.kept_off) * LPR;
   uint4 *Vo = reinterpret_cast<uint4 *>(c.V_out) + (unit * sh.SB + s.kept_off) * LPR;
-  for (int q = wave; q < n_tasks; q += kF3Waves) {
-    const int4 task = tasks[q];
-    const int *mem = members + task.y;
-    float ak[EPC], av[EPC];
+  constexpr int kGroups = kF3Waves * RPL;
+  const int gid = wave * RPL + rg;
+
+  // pivots nobody merges into: bit copies (needs no member list, so it runs before the barrier)
+  for (int base = 0; base < n_copy; base += kGroups * U) {  // the U loads of a pass are independent
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
-    const bool single = task.w < 0;
-    if (single && rg == 0) {
-      const int pivot_tok = kept[task.x];
-      chunk_to_floats<kBF16>(K[(long long)pivot_tok * sh.ks_tok + ch], ak);
-      chunk_to_floats<kBF16>(V[(long long)pivot_tok * sh.ks_tok + ch], av);
+    for (int u = 0; u < U; ++u) {
+      const int idx = base + u * kGroups + gid;
+      if (idx < n_copy) {
+        const int slot = copies[idx];
+        const int tok = lds_kept[slot];
+        const uint4 kc = K[(long long)tok * sh.ks_tok + ch];
+        const uint4 vc = V[(long long)tok * sh.ks_tok + ch];
+        Ko[(long long)slot * LPR + ch] = kc;
+        Vo[(long long)slot * LPR + ch] = vc;
+      }
     }
-    for (int j0 = rg; j0 < task.z; j0 += RPL * U) {
+  }
+  __syncthreads();
+  TRACE(3);
+
+  // Every group works on its own task, one batch of U rows per trip of the loop, and takes the
+  // next free task when it is done (large chunks come first in the list), so neither a long
+  // task nor an unlucky share holds anybody up.  Who computes a task does not change its sum.
+  int q = gid;
+  bool have = q < n_tasks;
+  int4 task = have ? tasks[q] : make_int4(0, 0, 0, 0);
+  int j0 = 0;
+  float ak[EPC], av[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
+  while (__any(have)) {
+    if (have) {
+      // rows of this task: the pivot itself first if the task finishes its slot, then the members
+      const int lead = task.w < 0 ? 1 : 0;
+      const int nrows = task.z + lead;
+      const int *mem = members + task.y - lead;
+      const int pivot_tok = lds_kept[task.x];
       int tokv[U];
       uint4 kc[U], vc[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int j = j0 + u * RPL;
-        tokv[u] = j < task.z ? mem[j] : -1;
+        const int j = j0 + u;
+        tokv[u] = j < nrows ? (j < lead ? pivot_tok : mem[j]) : -1;
       }
 #pragma unroll
       for (int u = 0; u < U; ++u)
@@ -503,49 +580,54 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
 #pragma unroll
           for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
         }
-    }
+      j0 += U;
+      if (j0 >= nrows) {  // task finished: write its result, move to the next one of this group
+        if (lead) {
+          const float w = 1.0f / (float)(1 + task.z);  // uniform merge weight
 #pragma unroll
-    for (int o = LPR; o < 64; o <<= 1)
+          for (int e = 0; e < EPC; ++e) { ak[e] *= w; av[e] *= w; }
+          Ko[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(ak);
+          Vo[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(av);
+        } else {
+          float *pp = partials + (long long)task.w * 2 * D + ch * EPC;
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) {
-        ak[e] += __shfl_xor(ak[e], o, 64);
-        av[e] += __shfl_xor(av[e], o, 64);
-      }
-    if (rg == 0) {
-      if (single) {
-        const float den = (float)(1 + task.z);
+          for (int e = 0; e < EPC; ++e) { pp[e] = ak[e]; pp[D + e] = av[e]; }
+        }
+        int nq = 0;
+        if (ch == 0) nq = atomicAdd(&sh_next, 1);
+        q = __shfl(nq, rg * LPR, 64);
+        have = q < n_tasks;
+        if (have) task = tasks[q];
+        j0 = 0;
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) { ak[e] = ak[e] / den; av[e] = av[e] / den; }
-        Ko[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(ak);
-        Vo[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(av);
-      } else {
-        float *p = partials + (long long)task.w * 2 * D + ch * EPC;
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) { p[e] = ak[e]; p[D + e] = av[e]; }
+        for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
       }
     }
   }
+  TRACE(4);
   __syncthreads();
+  TRACE(5);
   // slots cut into several tasks: pivot row plus the partials in task order
-  for (int q = wave; q < n_multi; q += kF3Waves) {
-    const int4 e4 = multi[q];  // (slot, first partial, partials, members)
-    const int pivot_tok = kept[e4.x];
-    const float den = (float)(1 + e4.w);
+  for (int qm = wave; qm < n_multi; qm += kF3Waves) {
+    const int4 e4 = multi[qm];
+    const int pivot_tok = lds_kept[e4.x];
+    const float w = 1.0f / (float)(1 + e4.w);
     if (lane < 2 * LPR) {
       const int tensor = lane / LPR, cch = lane % LPR;
       const uint4 *src = tensor ? V : K;
       float acc[EPC];
       chunk_to_floats<kBF16>(src[(long long)pivot_tok * sh.ks_tok + cch], acc);
-      for (int p = 0; p < e4.z; ++p) {
-        const float *pp = partials + (long long)(e4.y + p) * 2 * D + tensor * D + cch * EPC;
+      for (int pi = 0; pi < e4.z; ++pi) {
+        const float *pp = partials + (long long)(e4.y + pi) * 2 * D + tensor * D + cch * EPC;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) acc[e] += pp[e];
       }
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[e] = acc[e] / den;
+      for (int e = 0; e < EPC; ++e) acc[e] *= w;
       (tensor ? Vo : Ko)[(long long)e4.x * LPR + cch] = floats_to_chunk<kBF16>(acc);
     }
   }
+  TRACE(6);
 }
 
 // ---- dispatch --------------------------------------------------------------------------------
@@ -592,6 +674,12 @@ hipError_t launch_f3(const Ctx &c) {
 }
 
 }  // namespace
+
+#ifdef FLOWMM_TRACE
+extern "C" __attribute__((visibility("default"))) int flowmm_trace_set(void *p) {
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p));
+}
+#endif
 
 bool unit_path_fits(const Shape &sh) {
   if (!sh.bf16 || sh.maxL > 1024 || sh.R_pad > 64 || sh.maxB > 256 || sh.Hq > 4096) return false;
