@@ -44,7 +44,7 @@ hipError_t launch_merge(const Ctx &c);    // CSR build, task sums, combine
 
 // unit-resident path (short prompts): one workgroup per (sequence, kv head, layer)
 bool unit_path_fits(const Shape &sh);
-hipError_t launch_unit_plan(const Ctx &c);   // score+select, flow+match
+hipError_t launch_unit_plan(const Ctx &c);   // score, flow+select+match
 hipError_t launch_unit_merge(const Ctx &c);
 
 // static LDS needs, used by the host to reject shapes that cannot be staged

@@ -49,6 +49,10 @@ __device__ __forceinline__ T block_exclusive_scan(T v, T *lds_wave /*[THREADS/64
 // keys: L float bit patterns (LDS or global).  Writes kept[0..B) ascending and assign[0..L)
 // (pivot: its slot; others: -2 = still to be matched).  All THREADS threads must call.
 template <int THREADS>
+__device__ __forceinline__ void compact_top_b(const unsigned *keys, int L, int W, unsigned thr, int need_eq,
+                                              int *kept, int *assign, SelectScratch<THREADS> &sc);
+
+template <int THREADS>
 __device__ __forceinline__ void select_top_b(const unsigned *keys, int L, int W, int B, int *kept,
                                              int *assign, SelectScratch<THREADS> &sc) {
   static_assert(THREADS >= 256 && THREADS % 64 == 0, "the digit scan uses one thread per bin");
@@ -98,7 +102,15 @@ __device__ __forceinline__ void select_top_b(const unsigned *keys, int L, int W,
     thr = prefix;
     need_eq = remaining;  // how many tokens equal to the threshold are still pivots
   }
+  compact_top_b<THREADS>(keys, L, W, thr, need_eq, kept, assign, sc);
+}
 
+// Ordered compaction given the threshold: tokens above it and the first need_eq tokens equal to it
+// are pivots, and so are the last W tokens.
+template <int THREADS>
+__device__ __forceinline__ void compact_top_b(const unsigned *keys, int L, int W, unsigned thr, int need_eq,
+                                              int *kept, int *assign, SelectScratch<THREADS> &sc) {
+  const int nbody = L - W;
   int gt_carry = 0, eq_carry = 0;
   for (int i0 = 0; i0 < L; i0 += THREADS) {
     const int i = i0 + threadIdx.x;
@@ -125,6 +137,186 @@ __device__ __forceinline__ void select_top_b(const unsigned *keys, int L, int W,
     gt_carry += total & 0xffff;
     eq_carry += total >> 16;
   }
+}
+
+// ---- wave64 reductions on the data-parallel-primitive path (no LDS traffic) ---------------------
+// dpp_ctrl: row_shr:n = 0x110 + n (shift right inside each row of 16 lanes), row_bcast:15 = 0x142
+// (lane 15 of every row to the next row), row_bcast:31 = 0x143 (lane 31 to the upper half).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float old, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_move(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// maximum over each half-wave (lanes 0..31, 32..63); valid in lanes 31 and 63
+__device__ __forceinline__ float half_wave_max_hi(float v) {
+  v = fmaxf(v, dpp_move<0x111, 0xf>(v, v));
+  v = fmaxf(v, dpp_move<0x112, 0xf>(v, v));
+  v = fmaxf(v, dpp_move<0x114, 0xf>(v, v));
+  v = fmaxf(v, dpp_move<0x118, 0xf>(v, v));
+  v = fmaxf(v, dpp_move<0x142, 0xa>(v, v));
+  return v;
+}
+
+// sum over each half-wave; valid in lanes 31 and 63
+__device__ __forceinline__ float half_wave_sum_hi(float v) {
+  v += dpp_move<0x111, 0xf>(0.f, v);
+  v += dpp_move<0x112, 0xf>(0.f, v);
+  v += dpp_move<0x114, 0xf>(0.f, v);
+  v += dpp_move<0x118, 0xf>(0.f, v);
+  v += dpp_move<0x142, 0xa>(0.f, v);
+  return v;
+}
+
+// sum over the wave; valid in lane 63
+__device__ __forceinline__ int wave_sum_hi(int v) {
+  v += dpp_move<0x111, 0xf>(0, v);
+  v += dpp_move<0x112, 0xf>(0, v);
+  v += dpp_move<0x114, 0xf>(0, v);
+  v += dpp_move<0x118, 0xf>(0, v);
+  v += dpp_move<0x142, 0xa>(0, v);
+  v += dpp_move<0x143, 0xc>(0, v);
+  return v;
+}
+
+// inclusive prefix sum over the wave in lane order
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_move<0x111, 0xf>(0, v);
+  v += dpp_move<0x112, 0xf>(0, v);
+  v += dpp_move<0x114, 0xf>(0, v);
+  v += dpp_move<0x118, 0xf>(0, v);
+  v += dpp_move<0x142, 0xa>(0, v);
+  v += dpp_move<0x143, 0xc>(0, v);
+  return v;
+}
+
+template <int THREADS>
+struct SmallSelectScratch {
+  int hist[4][256];  // one histogram per radix pass, cleared once
+  int wave_sums[THREADS / 64 + 1];
+};
+
+// Top-B split for L <= 4 * THREADS with few barriers: every thread keeps its four consecutive
+// keys in registers, each radix pass costs one barrier (the 256-bin scan is repeated by every
+// wave on its own instead of being shared), and the compaction is one block scan.
+// keys4: the thread's keys 4t..4t+3 (anything where 4t+j >= L).  Same results as select_top_b.
+template <int THREADS>
+__device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], int L, int W, int B, int *kept,
+                                                   int *assign, SmallSelectScratch<THREADS> &sc) {
+  const int lane = threadIdx.x & 63;
+  const int nbody = L - W;
+  const int need = B - W;
+  const int i0 = threadIdx.x * 4;
+  unsigned thr = 0xffffffffu;
+  int need_eq = 0;
+  for (int i = threadIdx.x; i < 4 * 256; i += THREADS) (&sc.hist[0][0])[i] = 0;
+  __syncthreads();
+  if (need > 0) {
+    unsigned prefix = 0, mask = 0;
+    int remaining = need;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      int *hist = sc.hist[pass];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool act = i0 + j < nbody && (keys4[j] & mask) == prefix;
+        const int dg = (keys4[j] >> shift) & 255;
+        const unsigned long long am = __ballot(act);
+        if (am) {  // a whole wave on one digit is the common case for the exponent byte
+          const int first = __ffsll((long long)am) - 1;
+          const int d0 = __shfl(dg, first, 64);
+          if (__ballot(act && dg == d0) == am) {
+            if (lane == first) atomicAdd(&hist[d0], __popcll(am));
+          } else if (act) {
+            atomicAdd(&hist[dg], 1);
+          }
+        }
+      }
+      __syncthreads();
+      // every wave scans the bins in descending order by itself: lane j owns bins 255-4j .. 252-4j
+      int c4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) c4[j] = hist[255 - 4 * lane - j];
+      const int mine = c4[0] + c4[1] + c4[2] + c4[3];
+      int before = wave_inclusive_scan(mine) - mine;  // keys in higher bins
+      int digit = -1, rem_new = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (digit < 0 && before < remaining && remaining <= before + c4[j]) {
+          digit = 255 - 4 * lane - j;
+          rem_new = remaining - before;
+        }
+        before += c4[j];
+      }
+      const unsigned long long found = __ballot(digit >= 0);
+      const int src = __ffsll((long long)found) - 1;
+      digit = __shfl(digit, src, 64);
+      remaining = __shfl(rem_new, src, 64);
+      prefix |= (unsigned)digit << shift;
+      mask |= 255u << shift;
+    }
+    thr = prefix;
+    need_eq = remaining;
+  }
+  // ordered compaction: one block scan over (above, equal) counts of the threads' four keys
+  int gt4 = 0, eq4 = 0;
+  bool gtj[4], eqj[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = i0 + j;
+    gtj[j] = i < L && (i >= nbody || keys4[j] > thr);
+    eqj[j] = i < nbody && keys4[j] == thr;
+    gt4 += gtj[j];
+    eq4 += eqj[j];
+  }
+  int total;
+  const int before = block_exclusive_scan<THREADS, int>(gt4 | (eq4 << 16), sc.wave_sums, &total);
+  int gt_before = before & 0xffff, eq_before = before >> 16;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = i0 + j;
+    if (i < L) {
+      const bool is_kept = gtj[j] || (eqj[j] && eq_before < need_eq);
+      const int slot = gt_before + min(eq_before, need_eq);
+      if (is_kept) kept[slot] = i;
+      assign[i] = is_kept ? slot : -2;
+    }
+    gt_before += gtj[j];
+    eq_before += eqj[j];
+  }
+}
+
+// The need-th largest of keys[0..nbody) (nbody <= 1024), found by ONE wave that holds 16 keys
+// per lane and fixes the threshold bit by bit from the top; no barrier inside.  Returns the
+// threshold and how many keys equal to it are still needed (wave-uniform).
+__device__ __forceinline__ void wave_select_threshold(const unsigned *keys, int nbody, int need, unsigned *thr_out,
+                                                      int *need_eq_out) {
+  const int lane = threadIdx.x & 63;
+  unsigned k[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int i = lane * 16 + j;
+    k[j] = i < nbody ? keys[i] : 0u;  // padding keys are 0 and are masked by the index test below
+  }
+  const int mine = min(max(nbody - lane * 16, 0), 16);  // valid keys of this lane
+  unsigned thr = 0;
+  for (int bit = 30; bit >= 0; --bit) {  // keys are non-negative floats: bit 31 is clear
+    const unsigned cand = thr | (1u << bit);
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) cnt += (j < mine && k[j] >= cand) ? 1 : 0;
+    const int total = __builtin_amdgcn_readlane(wave_sum_hi(cnt), 63);
+    if (total >= need) thr = cand;
+  }
+  int gt = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) gt += (j < mine && k[j] > thr) ? 1 : 0;
+  *thr_out = thr;
+  *need_eq_out = need - __builtin_amdgcn_readlane(wave_sum_hi(gt), 63);
 }
 
 }  // namespace flowmm

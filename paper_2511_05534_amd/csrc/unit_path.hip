@@ -3,8 +3,8 @@
 // When one (sequence, layer, kv head) unit fits on a compute unit, the whole logits tile
 // (G*W rows x L keys) stays in MFMA accumulator registers, so the softmax needs no second pass
 // over K and no partial statistics in HBM, and every step of a unit runs inside one workgroup:
-//   unit_score_select : score + top-B split            (K read once)
-//   unit_match        : flow + cosine argmax            (K read once, pivots staged once)
+//   unit_score        : proxy attention -> importance   (K read once)
+//   unit_match        : flow + top-B split + cosine argmax (K read once, pivots staged once)
 //   unit_merge        : counting sort + segment sums    (K and V read once)
 // Three launches instead of ten.  The arithmetic is the same as in the generic kernels
 // (score.hip, select.hip, match.hip, merge.hip); see those files for the paper passages.
@@ -32,23 +32,20 @@ static __device__ unsigned long long *g_trace;
 #define TRACE(k)
 #endif
 
-// ============================ score + select ================================================
+// ============================ score ==========================================================
 constexpr int kF1Threads = 512;
 constexpr int kF1Waves = kF1Threads / 64;
 
 template <int D, int RB, int NT>
-__global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
+__global__ __launch_bounds__(kF1Threads) void unit_score_kernel(Ctx c) {
   using CF = Cfg<kBF16, D>;
   constexpr int NCH = CF::NCH, NF = CF::NF;
   constexpr int ROWS = RB * 32;
-  constexpr int LMAX = NT * kF1Waves * 32;
   __shared__ uint4 ldsq[ROWS * (NCH + 1)];
   __shared__ float lds_stat[kF1Waves][ROWS];
   __shared__ float lds_gstat[ROWS];
   __shared__ float lds_rowimg[ROWS];
   __shared__ float lds_cross[kF1Waves][RB];
-  __shared__ unsigned lds_keys[LMAX];
-  __shared__ SelectScratch<kF1Threads> scratch;
 
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
@@ -82,38 +79,46 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
                    (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
   f32x16_t acc[NT][RB];
   int keymod[NT];
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[j][rb][i] = 0.f;
+  // software pipeline over this wave's tiles: the loads of tile j+1 are in flight while tile j is multiplied
+  uint4 kf[2][NF];
+  auto issue = [&](int j, uint4 (&dst)[NF]) {
     const int key0 = (wave + kF1Waves * j) * 32;
     keymod[j] = 0;
     if (key0 < L) {
       const int key = min(key0 + n, L - 1);
       keymod[j] = mod[key];
       const uint4 *row = K + (long long)key * sh.ks_tok + half;
-      uint4 kf[NF];
 #pragma unroll
-      for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
+      for (int f = 0; f < NF; ++f) dst[f] = row[2 * f];
+    }
+  };
+  issue(0, kf[0]);
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    if (j + 1 < NT) issue(j + 1, kf[(j + 1) & 1]);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[j][rb][i] = 0.f;
+    if ((wave + kF1Waves * j) * 32 < L) {
 #pragma unroll
       for (int f = 0; f < NF; ++f)
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-          mma_chunk<kBF16>(acc[j][rb], ldsq[(rb * 32 + n) * (NCH + 1) + 2 * f + half], kf[f]);  // [query row][key]
+          mma_chunk<kBF16>(acc[j][rb], ldsq[(rb * 32 + n) * (NCH + 1) + 2 * f + half], kf[j & 1][f]);  // [query row][key]
     }
   }
 
   TRACE(2);
   // mask, move to the log2 domain, per-row maximum over this wave's keys
   const float cl = sh.scale_log2e;
+  const int wmask = sh.W_pad - 1;  // W_pad is 32 or 64 here
   float rowv[RB][16];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int r = (rb * 32 + acc_row(i, half)) % sh.W_pad;
+      const int r = (rb * 32 + acc_row(i, half)) & wmask;
       const int limit = r < sh.W ? L - sh.W + r : -1;
       float m = -INFINITY;
 #pragma unroll
@@ -123,11 +128,9 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
         acc[j][rb][i] = v;
         m = fmaxf(m, v);
       }
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-      rowv[rb][i] = m;
+      rowv[rb][i] = half_wave_max_hi(m);
     }
-  if (n == 0) {
+  if (n == 31) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -155,11 +158,9 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
         acc[j][rb][i] = e;
         z += e;
       }
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) z += __shfl_xor(z, o, 64);
-      rowv[rb][i] = z;
+      rowv[rb][i] = half_wave_sum_hi(z);
     }
-  if (n == 0) {
+  if (n == 31) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -206,10 +207,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
     }
     const float tot = (colsum + __shfl_xor(colsum, 32, 64)) * inv_rows;
     const int key = (wave + kF1Waves * j) * 32 + n;
-    if (half == 0 && key < L) {
-      imp[key] = tot;
-      lds_keys[key] = __float_as_uint(tot);
-    }
+    if (half == 0 && key < L) imp[key] = tot;
   }
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
@@ -227,42 +225,84 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_select_kernel(Ctx c) {
   }
 
   TRACE(4);
-  // top-B split on the importances still in LDS
-  int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
-  int *assign = c.assign + unit * sh.T + s.tok_off;
-  select_top_b<kF1Threads>(lds_keys, L, sh.W, s.B, kept, assign, scratch);
-  TRACE(5);
 }
 
-// ============================ flow + match ==================================================
+// ============================ flow + select + match =========================================
 constexpr int kF2Threads = 256;
 constexpr int kF2Waves = kF2Threads / 64;
+
+struct MatchLds {  // byte offsets into the dynamic LDS block
+  int piv, w, bias, head, keys, assign, kept, total_bytes;
+};
+
+__host__ __device__ inline MatchLds match_lds_layout(int b_pad, int nch, int Hq, int maxL) {
+  MatchLds m;
+  int off = 0;
+  m.piv = off; off += b_pad * (nch + 1) * 16;
+  m.w = off; off += b_pad * 4;
+  m.bias = off; off += 2 * b_pad * 4;
+  m.head = off; off += Hq * 4;
+  m.keys = off; off += maxL * 4;
+  m.assign = off; off += maxL * 4;
+  m.kept = off; off += b_pad * 4;
+  m.total_bytes = (off + 15) & ~15;
+  return m;
+}
 
 template <int D>
 __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad) {
   using CF = Cfg<kBF16, D>;
   constexpr int NCH = CF::NCH, NF = CF::NF;
-  extern __shared__ __align__(16) uint4 lds_dyn[];
-  uint4 *lds_piv = lds_dyn;                                                  // [b_pad][NCH+1]
-  float *lds_w = reinterpret_cast<float *>(lds_piv + b_pad * (NCH + 1));     // [b_pad]
-  float *lds_bias = lds_w + b_pad;                                           // [2][b_pad]
-  float *lds_head = lds_bias + 2 * b_pad;                                    // [Hq]
+  extern __shared__ __align__(16) char lds_dyn[];
+  const MatchLds lay = match_lds_layout(b_pad, NCH, c.sh.Hq, c.sh.maxL);
+  uint4 *lds_piv = reinterpret_cast<uint4 *>(lds_dyn + lay.piv);     // [b_pad][NCH+1] pivot rows
+  float *lds_w = reinterpret_cast<float *>(lds_dyn + lay.w);         // [b_pad] 1/norm (0 for a zero row)
+  float *lds_bias = reinterpret_cast<float *>(lds_dyn + lay.bias);   // [2][b_pad] 0 eligible, -inf not
+  float *lds_head = reinterpret_cast<float *>(lds_dyn + lay.head);   // [Hq]
+  unsigned *lds_keys = reinterpret_cast<unsigned *>(lds_dyn + lay.keys);  // [L] importance bits
+  int *lds_assign = reinterpret_cast<int *>(lds_dyn + lay.assign);   // [L] slot of a pivot, -2 otherwise
+  int *lds_kept = reinterpret_cast<int *>(lds_dyn + lay.kept);       // [B]
+  __shared__ SmallSelectScratch<kF2Threads> scratch;
   __shared__ float sh_rho;
   __shared__ int sh_dropped;
 
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  TRACE(8);
   const SeqInfo s = load_seq(c.meta, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const long long unit = (long long)l * sh.Hkv + gkv;
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
+                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  const uint8_t *mod = c.mod + s.tok_off;
+  const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
+  int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  int *assign = c.assign + unit * sh.T + s.tok_off;
 
-  TRACE(8);
-  // flow: every workgroup of the layer folds the same numbers in the same order
+  // the first token tile of this wave is requested before anything else
+  const int ntiles = (L + 31) >> 5;
+  uint4 kf[NF];
+  int t = wave;
+  if (t < ntiles) {
+    const uint4 *row = K + (long long)min(t * 32 + n, L - 1) * sh.ks_tok + half;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
+  }
+
+  // importances (four consecutive keys per thread) and the heads' cross-modal shares arrive together
+  unsigned keys4[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = threadIdx.x * 4 + j;
+    keys4[j] = i < L ? imp[i] : 0u;
+    if (i < L) lds_keys[i] = keys4[j];
+  }
   for (int h = threadIdx.x; h < sh.Hq; h += kF2Threads)
     lds_head[h] = c.cross_part[(long long)(l * sh.Hq + h) * sh.tiles_score + b] / (float)sh.W;
   if (threadIdx.x == 0) sh_dropped = 0;
   __syncthreads();
+  // flow: every workgroup of the layer folds the same numbers in the same order
   if (threadIdx.x == 0) {
     float acc = 0.f;
     for (int h = 0; h < sh.Hq; ++h) acc += lds_head[h];
@@ -273,59 +313,43 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
       c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
     }
   }
+  TRACE(9);
+  // top-B split (pivot list and pivot/non-pivot marks stay in LDS; the plan gets its copy below)
+  select_top_b_small<kF2Threads>(keys4, L, sh.W, s.B, lds_kept, lds_assign, scratch);
   __syncthreads();
   const bool mode_cross = sh_rho > sh.theta;
-
-  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
-                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
-  const uint8_t *mod = c.mod + s.tok_off;
-  const float *imp = c.importance + unit * sh.T + s.tok_off;
-  const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
-  int *assign = c.assign + unit * sh.T + s.tok_off;
-
-  TRACE(9);
-  // first token tile of this wave is requested before the pivots are staged
-  const int ntiles = (L + 31) >> 5;
-  uint4 kf[NF];
-  int t = wave;
-  if (t < ntiles) {
-    const uint4 *row = K + (long long)min(t * 32 + n, L - 1) * sh.ks_tok + half;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
-  }
+  for (int i = threadIdx.x; i < s.B; i += kF2Threads) kept[i] = lds_kept[i];
+  TRACE(10);
 
   // stage all pivots once: rows, inverse norms, eligibility per token modality
   constexpr int kRowsPerPass = kF2Threads / NCH;
   for (int r0 = 0; r0 < b_pad; r0 += kRowsPerPass) {
     const int pr = r0 + threadIdx.x / NCH, ch = threadIdx.x % NCH;
     uint4 v = make_uint4(0, 0, 0, 0);
-    int ptok = 0;
     const bool real = pr < s.B;
-    if (real) {
-      ptok = kept[pr];
-      v = K[(long long)ptok * sh.ks_tok + ch];
-    }
+    const int ptok = real ? lds_kept[pr] : 0;
+    if (real) v = K[(long long)ptok * sh.ks_tok + ch];
+    const int pm = real ? mod[ptok] : 0;
     if (pr < b_pad) lds_piv[pr * (NCH + 1) + ch] = v;
     float ss = chunk_sumsq<kBF16>(v);
 #pragma unroll
     for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
     if (ch == 0 && pr < b_pad) {
-      const bool ok = real && !(imp[ptok] > s.tau);
-      const int pm = real ? mod[ptok] : 0;
+      const bool ok = real && !(__uint_as_float(lds_keys[ptok]) > s.tau);
       lds_w[pr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
       lds_bias[pr] = ok && (mode_cross || pm == 0) ? 0.f : -INFINITY;
       lds_bias[b_pad + pr] = ok && (mode_cross || pm == 1) ? 0.f : -INFINITY;
     }
   }
   __syncthreads();
+  TRACE(11);
 
-  TRACE(10);
   const int nblk = b_pad >> 5;
   int dropped = 0;
   for (; t < ntiles; t += kF2Waves) {
     const int tok = t * 32 + n;
     const int tc = min(tok, L - 1);
-    const int cur = assign[tc];
+    const int cur = lds_assign[tc];
     const float *bias = lds_bias + (mod[tc] ? b_pad : 0);
     uint4 nxt[NF];
     if (t + kF2Waves < ntiles) {
@@ -352,20 +376,19 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
     const float ob = __shfl_xor(best, 32, 64);
     const int os = __shfl_xor(best_slot, 32, 64);
     if (ob > best || (ob == best && (unsigned)os < (unsigned)best_slot)) { best = ob; best_slot = os; }
-    if (half == 0 && tok < L && cur == -2) {
-      assign[tok] = best_slot;
-      dropped += best_slot < 0;
+    if (half == 0 && tok < L) {
+      assign[tok] = cur == -2 ? best_slot : cur;  // a pivot keeps its own slot
+      dropped += cur == -2 && best_slot < 0;
     }
     if (t + kF2Waves < ntiles) {
 #pragma unroll
       for (int f = 0; f < NF; ++f) kf[f] = nxt[f];
     }
   }
-  TRACE(11);
+  TRACE(12);
   dropped = wave_sum_int(dropped);
   if (lane == 0 && dropped) atomicAdd(&sh_dropped, dropped);
   __syncthreads();
-  TRACE(12);
   if (threadIdx.x == 0) c.n_dropped[unit * sh.batch + b] = sh_dropped;
 }
 
@@ -634,19 +657,18 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
 template <int D, int RB>
 hipError_t launch_f1(const Ctx &c, int nt) {
   const dim3 grid(c.sh.batch, c.sh.Hkv, c.sh.n_layers);
-  ProfScope ps(c.stream, KID_UNIT_SCORE_SELECT);
+  ProfScope ps(c.stream, KID_UNIT_SCORE);
   switch (nt) {
-    case 1: unit_score_select_kernel<D, RB, 1><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-    case 2: unit_score_select_kernel<D, RB, 2><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-    case 3: unit_score_select_kernel<D, RB, 3><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-    default: unit_score_select_kernel<D, RB, 4><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    case 1: unit_score_kernel<D, RB, 1><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    case 2: unit_score_kernel<D, RB, 2><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    case 3: unit_score_kernel<D, RB, 3><<<grid, kF1Threads, 0, c.stream>>>(c); break;
+    default: unit_score_kernel<D, RB, 4><<<grid, kF1Threads, 0, c.stream>>>(c); break;
   }
   return hipGetLastError();
 }
 
 size_t match_lds_bytes(const Shape &sh, int b_pad) {
-  const int nch = sh.d * 2 / 16;
-  return (size_t)b_pad * (nch + 1) * 16 + (size_t)b_pad * 3 * 4 + (size_t)sh.Hq * 4;
+  return (size_t)match_lds_layout(b_pad, sh.d * 2 / 16, sh.Hq, sh.maxL).total_bytes;
 }
 
 template <int D>
