@@ -138,4 +138,23 @@ __device__ __forceinline__ SeqInfo load_seq(const int *__restrict__ meta, int b)
   return s;
 }
 
+__device__ __forceinline__ SeqInfo inline_seq(const InlineMeta &m, int b) {
+  SeqInfo s;
+  s.tok_off = m.tok_off[b];
+  s.L = m.L[b];
+  s.B = m.B[b];
+  s.kept_off = m.kept_off[b];
+  s.tau = m.tau[b];
+  s.win_has_img = 0;  // unused by the kernels that take inline metadata
+  return s;
+}
+
+// modality (0 text, 1 image) of position i of sequence b: the first span that ends after i
+__device__ __forceinline__ int inline_mod(const InlineMeta &m, int b, int i) {
+  int j = m.span_off[b];
+  const int last = m.span_off[b + 1] - 1;
+  while (j < last && i >= m.span_end[j]) ++j;
+  return (m.span_is_image >> j) & 1u;
+}
+
 }  // namespace flowmm

@@ -29,6 +29,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
   Shape sh;
+  InlineMeta inl;
   Regions rg;
   std::vector<int32_t> words;
   size_t plan_bytes[6];
@@ -124,10 +125,24 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   const int n_spans = p->cu_spans[batch];
   const int64_t units = (int64_t)sh.n_layers * sh.Hkv;
   if (units * T >= (int64_t)1 << 40) return fail(FLOWMM_EUNSUPPORTED, "cache too large");
-  sh.T = (int)T; sh.SB = (int)sumB; sh.maxB = maxB; sh.maxL = maxL; sh.maxE = maxE;
+  sh.T = (int)T; sh.SB = (int)sumB; sh.maxB = maxB; sh.maxL = maxL; sh.maxE = maxE; sh.n_spans = n_spans;
   sh.unit_path = !(p->flags & FLOWMM_FLAG_GENERIC_PATH) && unit_path_fits(sh);
-  if (sh.unit_path)  // one score tile per sequence: its workgroup sees every key
-    for (int b = 0; b <= batch; ++b) cu_score[b] = b;
+  std::memset(&lo.inl, 0, sizeof(lo.inl));
+  if (sh.unit_path) {
+    for (int b = 0; b <= batch; ++b) cu_score[b] = b;  // one score tile per sequence
+    InlineMeta &m = lo.inl;
+    for (int b = 0; b < batch; ++b) {
+      const int32_t *r = &seq[(size_t)b * SW_WORDS];
+      m.tok_off[b] = r[SW_TOK_OFF]; m.L[b] = r[SW_L]; m.B[b] = r[SW_B]; m.kept_off[b] = r[SW_KEPT_OFF];
+      m.tau[b] = p->tau[b];
+      m.span_off[b] = p->cu_spans[b];
+    }
+    m.span_off[batch] = n_spans;
+    for (int j = 0; j < n_spans; ++j) {
+      m.span_end[j] = p->spans[j].end;
+      if (p->spans[j].modality == FLOWMM_IMAGE) m.span_is_image |= 1u << j;
+    }
+  }
   sh.tiles_score = cu_score[batch]; sh.tiles_match = cu_match[batch];
   sh.tasks_total = cu_task[batch]; sh.multi_total = cu_multi[batch]; sh.part_total = cu_part[batch];
   if (score_lds_bytes(sh) > kLdsLimit)
@@ -211,6 +226,7 @@ flowmm_status check_plan_buffers(const flowmm_plan_buffers *plan) {
 void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *workspace, void *stream) {
   std::memset(&c, 0, sizeof(c));
   c.sh = lo.sh;
+  c.inl = lo.inl;
   c.stream = reinterpret_cast<hipStream_t>(stream);
   c.importance = plan->importance; c.rho = plan->rho; c.mode = plan->mode;
   c.kept_idx = plan->kept_idx; c.assign = plan->assign; c.n_dropped = plan->n_dropped;
@@ -266,11 +282,11 @@ FLOWMM_API flowmm_status flowmm_plan(const flowmm_params *p, const void *K, cons
   fill_ctx(c, lo, plan, workspace, stream);
   c.K = K; c.Q = Q_window;
   hipError_t e;
-  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
   if (c.sh.unit_path) {
     if ((e = launch_unit_plan(c)) != hipSuccess) return hip_fail(e, "unit-resident plan kernels");
     return FLOWMM_OK;
   }
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
   if ((e = launch_score(c)) != hipSuccess) return hip_fail(e, "score kernels");
   if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
   if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
@@ -302,8 +318,12 @@ FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_
   fill_ctx(c, lo, plan, workspace, stream);
   c.K = K; c.V = V; c.K_out = K_out; c.V_out = V_out;
   hipError_t e;
+  if (c.sh.unit_path) {
+    if ((e = launch_unit_merge(c)) != hipSuccess) return hip_fail(e, "unit-resident merge kernel");
+    return FLOWMM_OK;
+  }
   if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), false)) != hipSuccess) return hip_fail(e, "metadata upload");
-  if ((e = c.sh.unit_path ? launch_unit_merge(c) : launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
+  if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
   return FLOWMM_OK;
 }
 

@@ -10,6 +10,7 @@ namespace flowmm {
 
 struct Ctx {
   Shape sh;
+  InlineMeta inl;  // valid when sh.unit_path
   hipStream_t stream;
   // inputs
   const void *K, *V, *Q;

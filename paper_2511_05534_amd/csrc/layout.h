@@ -48,12 +48,24 @@ constexpr int kCsrWaves = 16;                                // waves of the CSR
 
 struct Shape {
   int n_layers, Hq, Hkv, G, d, bf16;
-  int batch, T, SB, W, W_pad, R_pad, maxB, maxL, maxE;
+  int batch, T, SB, W, W_pad, R_pad, maxB, maxL, maxE, n_spans;
   int unit_path;  // 1: every unit is handled by one workgroup (unit_path.hip)
   int tiles_score, tiles_match, tasks_total, multi_total, part_total;
   float scale_log2e, theta;
   long long ks_layer, ks_head, ks_tok;  // K/V strides in 16-byte chunks
   long long qs_layer, qs_head, qs_tok;  // Q strides in 16-byte chunks
+};
+
+// Metadata small enough to ride in the kernel arguments (the unit-resident kernels use only this,
+// so short prompts need no upload launch): per-sequence records and the modality spans.
+constexpr int kInlineSeqs = 8;
+constexpr int kInlineSpans = 32;
+struct InlineMeta {
+  int tok_off[kInlineSeqs], L[kInlineSeqs], B[kInlineSeqs], kept_off[kInlineSeqs];
+  float tau[kInlineSeqs];
+  int span_off[kInlineSeqs + 1];  // spans of sequence b: [span_off[b], span_off[b+1])
+  int span_end[kInlineSpans];     // exclusive end of each span, position local to its sequence
+  unsigned span_is_image;         // bit j: span j holds image tokens
 };
 
 // byte offsets into the workspace (all multiples of 256)

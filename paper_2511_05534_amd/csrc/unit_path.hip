@@ -1,4 +1,5 @@
-// Unit-resident path for short prompts (bf16, every L <= 1024, G*W_pad <= 64, every B <= 256).
+// Unit-resident path for short prompts (bf16, every L <= 1024, G*W_pad <= 64, every B <= 256,
+// at most 8 sequences and 32 modality spans, whose description rides in the kernel arguments).
 //
 // When one (sequence, layer, kv head) unit fits on a compute unit, the whole logits tile
 // (G*W rows x L keys) stays in MFMA accumulator registers, so the softmax needs no second pass
@@ -50,11 +51,10 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_kernel(Ctx c) {
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
   TRACE(0);
-  const SeqInfo s = load_seq(c.meta, b);
+  const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const long long unit = (long long)l * sh.Hkv + gkv;
-  const uint8_t *mod = c.mod + s.tok_off;
 
   // stage the query rows (zero rows pad every head to a multiple of 32)
   {
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_kernel(Ctx c) {
     }
     for (int row = threadIdx.x; row < ROWS; row += kF1Threads) {
       const int r = row % sh.W_pad;
-      lds_rowimg[row] = (r < sh.W && mod[L - sh.W + r]) ? 1.f : 0.f;
+      lds_rowimg[row] = (r < sh.W && inline_mod(c.inl, b, L - sh.W + r)) ? 1.f : 0.f;
     }
   }
   __syncthreads();
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kF1Threads) void unit_score_kernel(Ctx c) {
     keymod[j] = 0;
     if (key0 < L) {
       const int key = min(key0 + n, L - 1);
-      keymod[j] = mod[key];
+      keymod[j] = inline_mod(c.inl, b, key);
       const uint4 *row = K + (long long)key * sh.ks_tok + half;
 #pragma unroll
       for (int f = 0; f < NF; ++f) dst[f] = row[2 * f];
@@ -269,13 +269,12 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
   TRACE(8);
-  const SeqInfo s = load_seq(c.meta, b);
+  const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const long long unit = (long long)l * sh.Hkv + gkv;
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
                    (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
-  const uint8_t *mod = c.mod + s.tok_off;
   const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
@@ -329,7 +328,7 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
     const bool real = pr < s.B;
     const int ptok = real ? lds_kept[pr] : 0;
     if (real) v = K[(long long)ptok * sh.ks_tok + ch];
-    const int pm = real ? mod[ptok] : 0;
+    const int pm = real ? inline_mod(c.inl, b, ptok) : 0;
     if (pr < b_pad) lds_piv[pr * (NCH + 1) + ch] = v;
     float ss = chunk_sumsq<kBF16>(v);
 #pragma unroll
@@ -350,7 +349,7 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
     const int tok = t * 32 + n;
     const int tc = min(tok, L - 1);
     const int cur = lds_assign[tc];
-    const float *bias = lds_bias + (mod[tc] ? b_pad : 0);
+    const float *bias = lds_bias + (inline_mod(c.inl, b, tc) ? b_pad : 0);
     uint4 nxt[NF];
     if (t + kF2Waves < ntiles) {
       const uint4 *row = K + (long long)min((t + kF2Waves) * 32 + n, L - 1) * sh.ks_tok + half;
@@ -451,7 +450,7 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
 
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
-  const SeqInfo s = load_seq(c.meta, b);
+  const SeqInfo s = inline_seq(c.inl, b);
   const long long unit = (long long)l * sh.Hkv + gkv;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int *assign = c.assign + unit * sh.T + s.tok_off;
@@ -705,6 +704,7 @@ extern "C" __attribute__((visibility("default"))) int flowmm_trace_set(void *p) 
 
 bool unit_path_fits(const Shape &sh) {
   if (!sh.bf16 || sh.maxL > 1024 || sh.R_pad > 64 || sh.maxB > 256 || sh.Hq > 4096) return false;
+  if (sh.batch > kInlineSeqs || sh.n_spans > kInlineSpans) return false;  // metadata must fit the kernel arguments
   const int b_pad = (sh.maxB + 31) / 32 * 32;
   if (match_lds_bytes(sh, b_pad) > 150 * 1024) return false;
   if ((size_t)merge_lds_layout(sh.maxB, sh.maxE, sh.d).total_bytes > 150 * 1024) return false;
