@@ -48,6 +48,19 @@ def algorithmic_bytes(wl):
     return tot
 
 
+def measured_traffic(config: int, kernel: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"unit_path_config{config}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = [x.strip() for x in line.split("|")]
+            if not line.startswith("#") and len(f) >= 4 and f[0] == kernel:
+                return float(f[3])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, budget_s: float):
     """Time the CPU oracle (as it stands) on whole layers of the same workload."""
     import oracle
@@ -78,6 +91,10 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the metric's configuration)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="measured HBM bytes per launch of the roofline kernel (from the rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -101,6 +118,13 @@ def main():
     def step():
         bufs.plan(K, Q, stream)
         bufs.merge(K, V, stream)
+
+    if args.pmc_calibrate:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # warm-up; its last steps are bracketed kernel by kernel to find the dominant one
     for _ in range(max(args.warmup - 5, 0)):
@@ -141,7 +165,8 @@ def main():
                    "window": wl.window, "theta": wl.theta, "tokens_per_step": wl.total_tokens,
                    "token_layer_kvheads_per_s": tokens_per_s * wl.n_layers * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": args.traffic_bytes if args.traffic_bytes is not None else measured_traffic(args.config, dominant),
                      "kernel_us": dom_us, "algorithmic_bytes_per_launch": alg.get(dominant, 0)},
         "full_pass": {"algorithmic_bytes": alg["whole_pass"],
                       "achieved_GBs": alg["whole_pass"] / (ms_per_step * 1e-3) / 1e9,
