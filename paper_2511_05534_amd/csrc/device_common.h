@@ -122,7 +122,7 @@ __device__ __forceinline__ int find_seq(const int *__restrict__ cu, int batch, i
 }
 
 struct SeqInfo {
-  int tok_off, L, B, kept_off, win_has_img;
+  int tok_off, L, B, kept_off, win_has_img, n_text;
   float tau;
 };
 
@@ -135,6 +135,7 @@ __device__ __forceinline__ SeqInfo load_seq(const int *__restrict__ meta, int b)
   s.kept_off = r[SW_KEPT_OFF];
   s.tau = __int_as_float(r[SW_TAU]);
   s.win_has_img = r[SW_WIN_HAS_IMG];
+  s.n_text = r[SW_N_TEXT];
   return s;
 }
 
@@ -146,6 +147,7 @@ __device__ __forceinline__ SeqInfo inline_seq(const InlineMeta &m, int b) {
   s.kept_off = m.kept_off[b];
   s.tau = m.tau[b];
   s.win_has_img = 0;  // unused by the kernels that take inline metadata
+  s.n_text = 0;
   return s;
 }
 

@@ -80,8 +80,9 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   sh.qs_layer = p->q_stride_layer / epc; sh.qs_head = p->q_stride_head / epc; sh.qs_tok = p->q_stride_token / epc;
 
   const int batch = p->batch;
+  const int match_tile = match_tile_tokens(sh.bf16);
   std::vector<int32_t> cu_score(batch + 1, 0), cu_match(batch + 1, 0), cu_task(batch + 1, 0),
-      cu_multi(batch + 1, 0), cu_part(batch + 1, 0);
+      cu_multi(batch + 1, 0), cu_part(batch + 1, 0), cu_bp(batch + 1, 0);
   std::vector<int32_t> seq((size_t)batch * SW_WORDS, 0);
   int64_t sumB = 0;
   int maxB = 0, maxL = 0, maxE = 0;
@@ -95,7 +96,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     if (std::isnan(p->tau[b])) return fail(FLOWMM_EINVAL, "tau[%d] is NaN", b);
     const int s0 = p->cu_spans[b], s1 = p->cu_spans[b + 1];
     if (s1 <= s0) return fail(FLOWMM_EINVAL, "sequence %d has no spans", b);
-    int pos = 0, win_img = 0;
+    int pos = 0, win_img = 0, n_text = 0;
     for (int j = s0; j < s1; ++j) {
       const flowmm_span &sp = p->spans[j];
       if (sp.begin != pos || sp.end <= sp.begin)
@@ -103,19 +104,22 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
       if (sp.modality != FLOWMM_TEXT && sp.modality != FLOWMM_IMAGE)
         return fail(FLOWMM_EINVAL, "span %d of sequence %d has modality %d", j - s0, b, sp.modality);
       if (sp.modality == FLOWMM_IMAGE && sp.end > L - p->window) win_img = 1;
+      if (sp.modality == FLOWMM_TEXT) n_text += sp.end - sp.begin;
       pos = sp.end;
     }
     if (pos != L) return fail(FLOWMM_EINVAL, "spans of sequence %d cover [0,%d), not [0,%d)", b, pos, L);
     const int E = L - B;
     cu_score[b + 1] = cu_score[b] + (L + kScoreTile - 1) / kScoreTile;
-    cu_match[b + 1] = cu_match[b] + (L + kMatchTile - 1) / kMatchTile;
+    // an intra-modal layer matches text and image tokens in separate tiles: one tile more at most
+    cu_match[b + 1] = cu_match[b] + (L + match_tile - 1) / match_tile + 1;
+    cu_bp[b + 1] = cu_bp[b] + (B + 31) / 32 * 32;
     cu_task[b + 1] = cu_task[b] + B + E / kTaskChunk + 1;
     cu_multi[b + 1] = cu_multi[b] + E / (kTaskChunk + 1) + 1;
     cu_part[b + 1] = cu_part[b] + 2 * (E / kTaskChunk) + 2;
     int32_t *r = &seq[(size_t)b * SW_WORDS];
     r[SW_TOK_OFF] = p->cu_seqlens[b]; r[SW_L] = L; r[SW_B] = B; r[SW_KEPT_OFF] = (int32_t)sumB;
     std::memcpy(&r[SW_TAU], &p->tau[b], 4);
-    r[SW_SPAN_OFF] = s0; r[SW_N_SPANS] = s1 - s0; r[SW_WIN_HAS_IMG] = win_img;
+    r[SW_SPAN_OFF] = s0; r[SW_N_SPANS] = s1 - s0; r[SW_WIN_HAS_IMG] = win_img; r[SW_N_TEXT] = n_text;
     sumB += B;
     if (B > maxB) maxB = B;
     if (L > maxL) maxL = L;
@@ -145,6 +149,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   }
   sh.tiles_score = cu_score[batch]; sh.tiles_match = cu_match[batch];
   sh.tasks_total = cu_task[batch]; sh.multi_total = cu_multi[batch]; sh.part_total = cu_part[batch];
+  sh.SBP = cu_bp[batch];
   if (score_lds_bytes(sh) > kLdsLimit)
     return fail(FLOWMM_EUNSUPPORTED, "(n_q_heads/n_kv_heads) x window = %d query rows per kv head do not fit in LDS", sh.R_pad);
   if (merge_csr_lds_bytes(maxB) > kLdsLimit)
@@ -168,6 +173,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   w[MW_OFF_CU_TASK] = append(cu_task);
   w[MW_OFF_CU_MULTI] = append(cu_multi);
   w[MW_OFF_CU_PART] = append(cu_part);
+  w[MW_OFF_CU_BP] = append(cu_bp);
 
   // plan buffers
   lo.plan_bytes[0] = (size_t)units * T * 4;
@@ -182,10 +188,19 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   size_t off = 0;
   rg.meta = off; off += align256(w.size() * 4);
   rg.mod = off; off += align256((size_t)T);
+  rg.cls_order = off; off += align256((size_t)T * 4);
   const size_t shared0 = off;
   rg.part_stats = off; off += align256((size_t)units * sh.tiles_score * sh.R_pad * sizeof(float2));
   rg.rowstat = off; off += align256((size_t)units * batch * sh.R_pad * sizeof(float2));
   rg.cross_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.tiles_score * 4);
+  if (!sh.unit_path) {
+    rg.pl_slot = off; off += align256((size_t)units * 2 * sh.SBP * 4);
+    rg.pl_w = off; off += align256((size_t)units * 2 * sh.SBP * 4);
+    rg.pl_n = off; off += align256((size_t)units * batch * 2 * 4);
+    rg.pack = off; off += align256((size_t)units * 2 * sh.SBP * sh.d * es);
+  } else {
+    rg.pl_slot = rg.pl_w = rg.pl_n = rg.pack = off;
+  }
   rg.plan_end = off;
   off = shared0;
   rg.seg_off = off; off += align256((size_t)units * (sumB + batch) * 4);
@@ -236,6 +251,11 @@ void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *w
   c.part_stats = reinterpret_cast<float2 *>(ws + lo.rg.part_stats);
   c.rowstat = reinterpret_cast<float2 *>(ws + lo.rg.rowstat);
   c.cross_part = reinterpret_cast<float *>(ws + lo.rg.cross_part);
+  c.cls_order = reinterpret_cast<int *>(ws + lo.rg.cls_order);
+  c.pl_slot = reinterpret_cast<int *>(ws + lo.rg.pl_slot);
+  c.pl_w = reinterpret_cast<float *>(ws + lo.rg.pl_w);
+  c.pl_n = reinterpret_cast<int *>(ws + lo.rg.pl_n);
+  c.pack = reinterpret_cast<uint4 *>(ws + lo.rg.pack);
   c.seg_off = reinterpret_cast<int *>(ws + lo.rg.seg_off);
   c.members = reinterpret_cast<int *>(ws + lo.rg.members);
   c.tasks = reinterpret_cast<int4 *>(ws + lo.rg.tasks);

@@ -21,10 +21,15 @@ struct Ctx {
   void *K_out, *V_out;
   // workspace regions
   int *meta;
-  uint8_t *mod;
+  uint8_t *mod;        // [T]                             modality of every packed token
+  int *cls_order;      // [T]                             per sequence: text positions ascending, then image positions
   float2 *part_stats;  // [Lyr][Hkv][tiles_score][R_pad]  (max, sum exp2) of each row over a tile
   float2 *rowstat;     // [Lyr][Hkv][batch][R_pad]        (max, 1/sum) of each row
   float *cross_part;   // [Lyr][Hq][tiles_score]          cross-modal mass of a head over a tile
+  int *pl_slot;        // [Lyr][Hkv][2*SBP]               eligible pivots per (sequence, token class): their slots, ascending
+  float *pl_w;         // [Lyr][Hkv][2*SBP]               1/norm of those pivots (0 for a zero row)
+  int *pl_n;           // [Lyr][Hkv][batch][2]            list lengths, padded to multiples of 32
+  uint4 *pack;         // [Lyr][Hkv][2*SBP][row chunks]   their K rows, chunk c of list row r at c ^ (r & (chunks-1))
   int *seg_off;        // [Lyr][Hkv][SB + batch]          CSR offsets of the members of each slot
   int *members;        // [Lyr][Hkv][T]                   evicted tokens grouped by slot, ascending
   int4 *tasks;         // [Lyr][Hkv][tasks_total]         (slot, first member, count, partial index or -1)

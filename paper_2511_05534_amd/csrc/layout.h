@@ -19,6 +19,7 @@ enum MetaWord {
   MW_OFF_CU_TASK,  // word offset of cu_tasks[batch+1]   (upper bounds)
   MW_OFF_CU_MULTI, // word offset of cu_multi[batch+1]   (upper bounds)
   MW_OFF_CU_PART,  // word offset of cu_part[batch+1]    (upper bounds)
+  MW_OFF_CU_BP,    // word offset of cu_bp[batch+1]      (budgets rounded up to 32, prefix sums)
   MW_HEADER = 16
 };
 
@@ -32,17 +33,19 @@ enum SeqWord {
   SW_SPAN_OFF,     // first span (index into spans)
   SW_N_SPANS,
   SW_WIN_HAS_IMG,  // 1 if any window row is an image token
-  SW_WORDS = 8
+  SW_N_TEXT,       // number of text tokens
+  SW_WORDS = 12
 };
 
 // tiling constants shared by host sizing and kernels
 constexpr int kScoreKeysPerWave = 64;
 constexpr int kScoreWaves = 4;
 constexpr int kScoreTile = kScoreKeysPerWave * kScoreWaves;  // keys per workgroup
-constexpr int kMatchTokPerWave = 64;
 constexpr int kMatchWaves = 4;
-constexpr int kMatchTile = kMatchTokPerWave * kMatchWaves;   // tokens per workgroup
-constexpr int kPivotTile = 128;                              // pivots staged in LDS at a time
+// 32-token groups a wave of the match kernel holds in registers (its MFMA B operands)
+constexpr int match_subs(bool bf16) { return bf16 ? 4 : 2; }
+constexpr int match_tile_tokens(bool bf16) { return kMatchWaves * 32 * match_subs(bf16); }  // tokens per workgroup
+constexpr int kPivotTileBytes = 32 * 1024;                   // packed pivot rows staged in LDS at a time
 constexpr int kTaskChunk = 32;                               // members summed by one wave task
 constexpr int kCsrWaves = 16;                                // waves of the CSR-building workgroup
 
@@ -50,6 +53,7 @@ struct Shape {
   int n_layers, Hq, Hkv, G, d, bf16;
   int batch, T, SB, W, W_pad, R_pad, maxB, maxL, maxE, n_spans;
   int unit_path;  // 1: every unit is handled by one workgroup (unit_path.hip)
+  int SBP;        // sum over sequences of the budget rounded up to a multiple of 32
   int tiles_score, tiles_match, tasks_total, multi_total, part_total;
   float scale_log2e, theta;
   long long ks_layer, ks_head, ks_tok;  // K/V strides in 16-byte chunks
@@ -70,7 +74,9 @@ struct InlineMeta {
 
 // byte offsets into the workspace (all multiples of 256)
 struct Regions {
-  size_t meta, mod, part_stats, rowstat, cross_part;       // plan
+  size_t meta, mod, cls_order;                              // both calls
+  size_t part_stats, rowstat, cross_part;                   // plan: score
+  size_t pl_slot, pl_w, pl_n, pack;                         // plan: match
   size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials;  // merge
   size_t plan_end, merge_end;
 };

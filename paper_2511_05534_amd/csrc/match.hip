@@ -3,131 +3,269 @@
 // layer, share its modality (FlowMM, Sensitivity-Adaptive Token Matching: cosine equation and
 // thresholded argmax; the intra/cross rule of Information Flow Guided Merging).
 //
-// The similarity matrix is never stored.  A workgroup owns 256 tokens (64 per wave, held as
-// MFMA operands in registers straight from HBM) and walks over the pivots in LDS-staged
-// tiles of 128 rows; each 32x32 block of dot products is scaled by the pivot's 1/norm, masked
-// by eligibility and folded into a running (best value, best slot) per token.  The token's own
-// norm is a positive factor common to all its candidates and is left out of the comparison.
+// Two kernels.
+//   lists : per (sequence, kv head, layer) the pivots that may receive tokens are listed per
+//           token class (one class in a cross-modal layer, text / image in an intra-modal one),
+//           in ascending slot order, padded to a multiple of 32 with copies of the first entry;
+//           their K rows are packed next to each other in the order and swizzle the match
+//           kernel's LDS tiles use, and their 1/norm is tabulated.  Ineligible pivots are not
+//           in any list, so the contraction below never meets them.
+//   match : a workgroup owns a tile of tokens of one class (32*KS per wave, held as MFMA B
+//           operands in registers straight from HBM) and walks over the class's pivot list in
+//           LDS tiles that arrive by direct global->LDS loads, double buffered.  The similarity
+//           matrix is never stored: each 32x32 block of dot products is scaled by the pivot's
+//           1/norm, shifted by the token's norm (so every candidate is a non-negative float whose
+//           bit pattern orders like its value) and folded into a running maximum whose low four
+//           mantissa bits carry the row inside the lane's share of the block.  The token's own
+//           norm is a positive factor common to all its candidates and is left out.
+//           Candidates therefore compare at 2^-19 relative resolution; below that the earlier
+//           list entry wins inside a lane's 16 rows of a block and the earlier block wins.
 #include "device_common.h"
 #include "kernels.h"
 #include "profile.h"
+#include "select_core.h"
 
 namespace flowmm {
 
 namespace {
 
 constexpr int kThreads = kMatchWaves * 64;
-constexpr int kSub = kMatchTokPerWave / 32;
+constexpr int kListSplit = 8;  // workgroups that share the row packing of one (sequence, kv head, layer)
+
+// Direct global -> LDS load: lane i of the wave fetches BYTES bytes from its own global address and
+// they land at lds_base + i * BYTES (lds_base wave-uniform).  Issued as inline assembly so that the
+// compiler does not wait for it before unrelated LDS reads (it cannot tell the two LDS buffers
+// apart; nothing else in these kernels uses M0); the caller waits with s_waitcnt vmcnt(0) and a barrier before reading the data.
+typedef __attribute__((address_space(3))) void lds_void;
+template <int BYTES>
+__device__ __forceinline__ void load_to_lds(const void *gptr, void *lds_base) {
+  const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
+  if constexpr (BYTES == 16)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads) void match_kernel(Ctx c) {
-  constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF;
-  __shared__ uint4 lds_piv[kPivotTile * (NCH + 1)];
-  __shared__ float lds_w[kPivotTile];         // 1/norm of the pivot (0 for a zero row)
-  __shared__ float lds_bias[2][kPivotTile];   // [token modality][pivot]: 0 eligible, -inf not
+__global__ __launch_bounds__(kThreads) void match_lists_kernel(Ctx c) {
+  constexpr int NCH = Cfg<BF16, D>::NCH;
+  __shared__ int lds_wave[kThreads / 64 + 1];
   const Shape &sh = c.sh;
   const int *meta = c.meta;
-  const int *cu = meta + meta[MW_OFF_CU_MATCH];
-  const int x = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
-  const int b = find_seq(cu, meta[MW_BATCH], x);
-  const int tile = x - cu[b];
+  const int b = blockIdx.x / kListSplit, part = blockIdx.x % kListSplit;
+  const int gkv = blockIdx.y, l = blockIdx.z;
   const SeqInfo s = load_seq(meta, b);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
-  const int tok0 = tile * kMatchTile + wave * kMatchTokPerWave;
   const long long unit = (long long)l * sh.Hkv + gkv;
-
+  const int Bp = (s.B + 31) & ~31;
+  const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b];
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
                    (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
   const uint8_t *mod = c.mod + s.tok_off;
   const float *imp = c.importance + unit * sh.T + s.tok_off;
   const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
-  int *assign = c.assign + unit * sh.T + s.tok_off;
-  const int mode_cross = c.mode[l * sh.batch + b];
+  int *pl_slot = c.pl_slot + lbase;
+  float *pl_w = c.pl_w + lbase;
+  uint4 *pack = c.pack + lbase * NCH;
+  const bool cross = c.mode[l * sh.batch + b] != 0;
 
-  // this wave's tokens as B operands
-  uint4 kf[kSub][NF];
-  int tok[kSub], tokmod[kSub];
-#pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) {
-    tok[sub] = tok0 + sub * 32 + n;
-    const int tc = tok[sub] < s.L ? tok[sub] : s.L - 1;
-    tokmod[sub] = mod[tc];
-    const uint4 *row = K + (long long)tc * sh.ks_tok + half;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) kf[sub][f] = row[2 * f];
+  // ordered placement of the eligible slots of each class.  Every workgroup of the split writes
+  // the same values, so each one can read its own copy back without waiting for the others.
+  int n[2] = {0, 0};
+  for (int s0 = 0; s0 < s.B; s0 += kThreads) {
+    const int slot = s0 + threadIdx.x;
+    int f0 = 0, f1 = 0;
+    if (slot < s.B) {
+      const int tok = kept[slot];
+      const bool ok = !(imp[tok] > s.tau);
+      const int cls = cross ? 0 : mod[tok];
+      f0 = ok && cls == 0;
+      f1 = ok && cls == 1;
+    }
+    int tot;
+    const int ex = block_exclusive_scan<kThreads, int>(f0 | (f1 << 16), lds_wave, &tot);
+    if (f0) pl_slot[n[0] + (ex & 0xffff)] = slot;
+    if (f1) pl_slot[Bp + n[1] + (ex >> 16)] = slot;
+    n[0] += tot & 0xffff;
+    n[1] += tot >> 16;
   }
-  float best[kSub];
-  int best_slot[kSub];
+  __syncthreads();
+  const int np[2] = {(n[0] + 31) & ~31, (n[1] + 31) & ~31};
 #pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) { best[sub] = -INFINITY; best_slot[sub] = -1; }
+  for (int cls = 0; cls < 2; ++cls)
+    for (int e = n[cls] + threadIdx.x; e < np[cls]; e += kThreads) pl_slot[cls * Bp + e] = pl_slot[cls * Bp];
+  if (part == 0 && threadIdx.x < 2) c.pl_n[(unit * sh.batch + b) * 2 + threadIdx.x] = np[threadIdx.x];
+  __syncthreads();
 
-  for (int p0 = 0; p0 < s.B; p0 += kPivotTile) {
-    const int np = min(kPivotTile, s.B - p0);
-    __syncthreads();  // previous tile fully consumed
-    // stage pivot rows, their inverse norms and eligibility
-    constexpr int kRowsPerPass = kThreads / NCH;
-    for (int r0 = 0; r0 < kPivotTile; r0 += kRowsPerPass) {
-      const int pr = r0 + threadIdx.x / NCH, ch = threadIdx.x % NCH;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      int ptok = 0;
-      if (pr < np) {
-        ptok = kept[p0 + pr];
-        v = K[(long long)ptok * sh.ks_tok + ch];
-      }
-      lds_piv[pr * (NCH + 1) + ch] = v;
+  // rows and inverse norms: NCH lanes per row, this workgroup takes every kListSplit-th pass
+  constexpr int RPP = kThreads / NCH;  // rows per pass; divides 32, so a pass is all real rows or none
+  const int rl = threadIdx.x / NCH, ch = threadIdx.x % NCH;
+#pragma unroll
+  for (int cls = 0; cls < 2; ++cls) {
+    for (int e0 = part * RPP; e0 < np[cls]; e0 += kListSplit * RPP) {
+      const int e = e0 + rl;
+      const int tok = kept[pl_slot[cls * Bp + e]];
+      const uint4 v = K[(long long)tok * sh.ks_tok + ch];
       float ss = chunk_sumsq<BF16>(v);
 #pragma unroll
       for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      if (ch == 0) {
-        const bool real = pr < np;
-        const bool sensitive = real && imp[ptok] > s.tau;
-        const int pm = real ? mod[ptok] : 0;
-        lds_w[pr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-        const bool ok = real && !sensitive;
-        lds_bias[0][pr] = ok && (mode_cross || pm == 0) ? 0.f : -INFINITY;
-        lds_bias[1][pr] = ok && (mode_cross || pm == 1) ? 0.f : -INFINITY;
-      }
+      pack[(long long)(cls * Bp + e) * NCH + (ch ^ (e & (NCH - 1)))] = v;
+      if (ch == 0) pl_w[cls * Bp + e] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
     }
-    __syncthreads();
-    const int nblk = (np + 31) >> 5;
-    for (int pb = 0; pb < nblk; ++pb) {
-      f32x16_t acc[kSub];
+  }
+}
+
+template <bool BF16, int D>
+__global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
+  using CF = Cfg<BF16, D>;
+  constexpr int NCH = CF::NCH, NF = CF::NF;
+  constexpr int KS = match_subs(BF16);
+  constexpr int TILE = kMatchWaves * 32 * KS;
+  constexpr int ROWS = kPivotTileBytes / (NCH * 16);  // list rows per LDS tile
+  extern __shared__ uint4 lds[];
+  uint4 *lds_rows = lds;                                             // [2][ROWS][NCH]
+  float *lds_w = reinterpret_cast<float *>(lds + 2 * ROWS * NCH);    // [2][ROWS]
+
+  const Shape &sh = c.sh;
+  const int *meta = c.meta;
+  // Workgroups are handed to the eight XCDs in turn.  All token tiles of a (layer, kv head) go to
+  // one XCD, so its pivot pack is fetched into one L2 only.
+  const int units = sh.n_layers * sh.Hkv;
+  const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+  const int ul = k / sh.tiles_match, x = k - ul * sh.tiles_match;
+  const int unit_i = ul * 8 + xcd;
+  if (unit_i >= units) return;
+  const int l = unit_i / sh.Hkv, gkv = unit_i - l * sh.Hkv;
+  const long long unit = unit_i;
+  const int *cu = meta + meta[MW_OFF_CU_MATCH];
+  const int b = find_seq(cu, meta[MW_BATCH], x);
+  int tile = x - cu[b];
+  const SeqInfo s = load_seq(meta, b);
+  const bool cross = c.mode[l * sh.batch + b] != 0;
+  // token class of this tile: everything in a cross-modal layer, else text tiles then image tiles
+  int cls = 0, cbeg = 0, cn = s.L;
+  if (!cross) {
+    const int t0 = (s.n_text + TILE - 1) / TILE;
+    if (tile < t0) {
+      cn = s.n_text;
+    } else {
+      tile -= t0; cls = 1; cbeg = s.n_text; cn = s.L - s.n_text;
+    }
+  }
+  const int v0 = tile * TILE;
+  if (v0 >= cn) return;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
+                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  const int *order = c.cls_order + s.tok_off + cbeg;
+  int *assign = c.assign + unit * sh.T + s.tok_off;
+  const int Bp = (s.B + 31) & ~31;
+  const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b] + cls * Bp;
+  const uint4 *pack = c.pack + lbase * NCH;
+  const float *pl_w = c.pl_w + lbase;
+  const int npc = c.pl_n[(unit * sh.batch + b) * 2 + cls];  // list length, a multiple of 32
+  const int ntiles = (npc + ROWS - 1) / ROWS;
+
+  auto stage = [&](int t, int buf) {
+    const int r0 = t * ROWS;
+    const int rows = min(ROWS, npc - r0);
+    const uint4 *src = pack + (long long)r0 * NCH;
+    uint4 *dst = lds_rows + buf * ROWS * NCH;
+    const int nchunks = rows * NCH;  // a multiple of 256
+    for (int q0 = wave * 64; q0 < nchunks; q0 += kThreads)
+      load_to_lds<16>(src + q0 + lane, dst + q0);
+    if (wave * 64 + lane < rows)
+      load_to_lds<4>(pl_w + r0 + wave * 64 + lane, lds_w + buf * ROWS + wave * 64);
+  };
+  if (ntiles > 0) stage(0, 0);
+
+  // this wave's tokens as B operands, and their norms
+  const int wv0 = v0 + wave * 32 * KS;
+  const bool active = wv0 < cn;
+  uint4 kf[KS][NF];
+  int tok[KS];
+  bool valid[KS];
+  float shift[KS];
 #pragma unroll
-      for (int sub = 0; sub < kSub; ++sub)
+  for (int sub = 0; sub < KS; ++sub) {
+    const int v = wv0 + sub * 32 + n;
+    valid[sub] = v < cn;
+    const int vc = min(v, cn - 1);
+    tok[sub] = cross ? vc : order[vc];
+    const uint4 *row = K + (long long)tok[sub] * sh.ks_tok + half;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) kf[sub][f] = row[2 * f];
+  }
+#pragma unroll
+  for (int sub = 0; sub < KS; ++sub) {
+    float ss = 0.f;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) ss += chunk_sumsq<BF16>(kf[sub][f]);
+    ss += __shfl_xor(ss, 32, 64);
+    shift[sub] = sqrtf(ss) * 1.001f;  // >= |<token, pivot>| / |pivot| for every pivot
+  }
+  unsigned best[KS];
+  int bblk[KS];
+#pragma unroll
+  for (int sub = 0; sub < KS; ++sub) { best[sub] = 0u; bblk[sub] = 0; }
+
+  for (int t = 0; t < ntiles; ++t) {
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's part of tile t has landed
+    __syncthreads();                // ... and everybody else's; tile t-1 is no longer read
+    if (t + 1 < ntiles) stage(t + 1, (t + 1) & 1);
+    if (!active) continue;
+    const uint4 *rows = lds_rows + (t & 1) * ROWS * NCH;
+    const float *wt = lds_w + (t & 1) * ROWS;
+    const int nblk = min(ROWS, npc - t * ROWS) >> 5;
+    for (int pb = 0; pb < nblk; ++pb) {
+      f32x16_t acc[KS];
+#pragma unroll
+      for (int sub = 0; sub < KS; ++sub)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[sub][i] = 0.f;
-      const uint4 *prow = lds_piv + (pb * 32 + n) * (NCH + 1) + half;
+      const int r = pb * 32 + n;
+      const uint4 *prow = rows + r * NCH;
+      const int sw = r & (NCH - 1);
 #pragma unroll
       for (int f = 0; f < NF; ++f) {
-        const uint4 pf = prow[2 * f];
+        const uint4 pf = prow[(2 * f + half) ^ sw];
 #pragma unroll
-        for (int sub = 0; sub < kSub; ++sub) mma_chunk<BF16>(acc[sub], pf, kf[sub][f]);  // [pivot][token]
+        for (int sub = 0; sub < KS; ++sub) mma_chunk<BF16>(acc[sub], pf, kf[sub][f]);  // [pivot][token]
       }
+      float w[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int pr = pb * 32 + acc_row(i, half);
-        const float w = lds_w[pr];
+      for (int g = 0; g < 4; ++g) {
+        const float4 w4 = *reinterpret_cast<const float4 *>(wt + pb * 32 + 8 * g + 4 * half);
+        w[4 * g] = w4.x; w[4 * g + 1] = w4.y; w[4 * g + 2] = w4.z; w[4 * g + 3] = w4.w;
+      }
+      const int blk = t * (ROWS / 32) + pb;
 #pragma unroll
-        for (int sub = 0; sub < kSub; ++sub) {
-          const float u = fmaf(acc[sub][i], w, lds_bias[tokmod[sub]][pr]);
-          if (u > best[sub]) { best[sub] = u; best_slot[sub] = p0 + pr; }  // ascending slots: first maximum stays
-        }
+      for (int sub = 0; sub < KS; ++sub) {
+        unsigned p[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          p[i] = (__float_as_uint(fmaf(acc[sub][i], w[i], shift[sub])) & ~15u) | (unsigned)(15 - i);
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) p[0] = max(max(p[0], p[i]), p[i + 1]);
+        if (p[0] > best[sub]) { best[sub] = p[0]; bblk[sub] = blk; }
       }
     }
   }
-  // the two half-waves saw disjoint pivot rows of the same token
+
+  // the two half-waves saw disjoint rows of the same tokens
+  const int *pl_slot = c.pl_slot + lbase;
   int dropped = 0;
 #pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) {
-    const float ob = __shfl_xor(best[sub], 32, 64);
-    const int os = __shfl_xor(best_slot[sub], 32, 64);
-    if (ob > best[sub] || (ob == best[sub] && (unsigned)os < (unsigned)best_slot[sub])) {
-      best[sub] = ob;
-      best_slot[sub] = os;
-    }
-    if (half == 0 && tok[sub] < s.L && assign[tok[sub]] == -2) {
-      assign[tok[sub]] = best_slot[sub];
-      dropped += best_slot[sub] < 0;
+  for (int sub = 0; sub < KS; ++sub) {
+    int e = bblk[sub] * 32 + acc_row(15 - (int)(best[sub] & 15u), half);
+    const unsigned mine = best[sub] >> 4;
+    const unsigned other = __shfl_xor(best[sub], 32, 64) >> 4;
+    const int oe = __shfl_xor(e, 32, 64);
+    if (other > mine || (other == mine && oe < e)) e = oe;
+    if (half == 0 && valid[sub] && assign[tok[sub]] == -2) {
+      const int slot = npc > 0 ? pl_slot[e] : -1;
+      assign[tok[sub]] = slot;
+      dropped += slot < 0;
     }
   }
   dropped = wave_sum_int(dropped);
@@ -136,8 +274,22 @@ __global__ __launch_bounds__(kThreads) void match_kernel(Ctx c) {
 
 template <bool BF16, int D>
 hipError_t launch_match_t(const Ctx &c) {
+  constexpr int NCH = Cfg<BF16, D>::NCH;
+  constexpr int ROWS = kPivotTileBytes / (NCH * 16);
+  const Shape &sh = c.sh;
+  {
+    ProfScope ps(c.stream, KID_MATCH_LISTS);
+    match_lists_kernel<BF16, D><<<dim3(sh.batch * kListSplit, sh.Hkv, sh.n_layers), kThreads, 0, c.stream>>>(c);
+  }
+  const size_t lds = 2 * (size_t)kPivotTileBytes + 2 * ROWS * sizeof(float);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(match_kernel<BF16, D>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  const int units = sh.n_layers * sh.Hkv;
+  const long long grid = (long long)((units + 7) / 8) * 8 * sh.tiles_match;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
   ProfScope ps(c.stream, KID_MATCH);
-  match_kernel<BF16, D><<<dim3(c.sh.tiles_match, c.sh.Hkv, c.sh.n_layers), kThreads, 0, c.stream>>>(c);
+  match_kernel<BF16, D><<<dim3((unsigned)grid), kThreads, lds, c.stream>>>(c);
   return hipGetLastError();
 }
 

@@ -13,8 +13,9 @@ __global__ __launch_bounds__(256) void meta_upload_kernel(MetaChunk chunk, int *
   for (int i = threadIdx.x; i < n; i += 256) dst[i] = chunk.w[i];
 }
 
-// one workgroup per span
-__global__ __launch_bounds__(256) void expand_modality_kernel(const int *meta, uint8_t *mod) {
+// one workgroup per span: the modality byte of its tokens, and their places in the sequence's
+// class order (all text positions ascending, then all image positions ascending)
+__global__ __launch_bounds__(256) void expand_modality_kernel(const int *meta, uint8_t *mod, int *cls_order) {
   const int batch = meta[MW_BATCH];
   const int *spans = meta + meta[MW_OFF_SPANS] + 3 * blockIdx.x;
   // owner sequence: the one whose span range contains this span
@@ -23,9 +24,18 @@ __global__ __launch_bounds__(256) void expand_modality_kernel(const int *meta, u
     const int *r = meta + meta[MW_OFF_SEQ] + i * SW_WORDS;
     if ((int)blockIdx.x >= r[SW_SPAN_OFF] && (int)blockIdx.x < r[SW_SPAN_OFF] + r[SW_N_SPANS]) b = i;
   }
-  const int tok_off = (meta + meta[MW_OFF_SEQ] + b * SW_WORDS)[SW_TOK_OFF];
+  const int *rec = meta + meta[MW_OFF_SEQ] + b * SW_WORDS;
+  const int tok_off = rec[SW_TOK_OFF];
   const uint8_t m = (uint8_t)spans[2];
-  for (int i = spans[0] + threadIdx.x; i < spans[1]; i += 256) mod[tok_off + i] = m;
+  int before = m ? rec[SW_N_TEXT] : 0;  // tokens of this class in earlier spans of the sequence
+  for (int j = rec[SW_SPAN_OFF]; j < (int)blockIdx.x; ++j) {
+    const int *sp = meta + meta[MW_OFF_SPANS] + 3 * j;
+    if (sp[2] == m) before += sp[1] - sp[0];
+  }
+  for (int i = spans[0] + threadIdx.x; i < spans[1]; i += 256) {
+    mod[tok_off + i] = m;
+    cls_order[tok_off + before + i - spans[0]] = i;
+  }
 }
 
 }  // namespace
@@ -40,7 +50,7 @@ hipError_t launch_meta_upload(const Ctx &c, const int *words, int n_words, bool 
   }
   if (expand_modality) {
     ProfScope ps(c.stream, KID_EXPAND_MODALITY);
-    expand_modality_kernel<<<words[MW_N_SPANS], 256, 0, c.stream>>>(c.meta, c.mod);
+    expand_modality_kernel<<<words[MW_N_SPANS], 256, 0, c.stream>>>(c.meta, c.mod, c.cls_order);
   }
   return hipGetLastError();
 }
