@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the metric's configuration)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="depth override for kernel tuning runs (0 = the configuration's own depth, which the metric needs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -108,7 +110,7 @@ def main():
         print("no GPU visible", file=sys.stderr)
         sys.exit(3)
     fb.load(build_if_missing=False)
-    wl = workloads.config(args.config)
+    wl = workloads.config(args.config, n_layers=args.layers or None)
     dev = "cuda:0"
     K, V, Q = fb.upload_workload(wl, dev)
     params = fb.Params.from_workload(wl)

@@ -197,7 +197,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     rg.pl_slot = off; off += align256((size_t)units * 2 * sh.SBP * 4);
     rg.pl_w = off; off += align256((size_t)units * 2 * sh.SBP * 4);
     rg.pl_n = off; off += align256((size_t)units * batch * 2 * 4);
-    rg.pack = off; off += align256((size_t)units * 2 * sh.SBP * sh.d * es);
+    rg.pack = off; off += align256((size_t)units * 2 * sh.SBP * (sh.d * es + 16));
   } else {
     rg.pl_slot = rg.pl_w = rg.pl_n = rg.pack = off;
   }

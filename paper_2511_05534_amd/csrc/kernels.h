@@ -29,7 +29,7 @@ struct Ctx {
   int *pl_slot;        // [Lyr][Hkv][2*SBP]               eligible pivots per (sequence, token class): their slots, ascending
   float *pl_w;         // [Lyr][Hkv][2*SBP]               1/norm of those pivots (0 for a zero row)
   int *pl_n;           // [Lyr][Hkv][batch][2]            list lengths, padded to multiples of 32
-  uint4 *pack;         // [Lyr][Hkv][2*SBP][row chunks]   their K rows, chunk c of list row r at c ^ (r & (chunks-1))
+  uint4 *pack;         // [Lyr][Hkv][2*SBP][row chunks+1] their K rows, one chunk of padding after each
   int *seg_off;        // [Lyr][Hkv][SB + batch]          CSR offsets of the members of each slot
   int *members;        // [Lyr][Hkv][T]                   evicted tokens grouped by slot, ascending
   int4 *tasks;         // [Lyr][Hkv][tasks_total]         (slot, first member, count, partial index or -1)

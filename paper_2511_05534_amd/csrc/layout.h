@@ -45,7 +45,8 @@ constexpr int kMatchWaves = 4;
 // 32-token groups a wave of the match kernel holds in registers (its MFMA B operands)
 constexpr int match_subs(bool bf16) { return bf16 ? 4 : 2; }
 constexpr int match_tile_tokens(bool bf16) { return kMatchWaves * 32 * match_subs(bf16); }  // tokens per workgroup
-constexpr int kPivotTileBytes = 32 * 1024;                   // packed pivot rows staged in LDS at a time
+// packed pivot rows staged in LDS at a time: 32 KB worth, 128 rows at most (nch = 16-byte chunks per row)
+constexpr int match_tile_rows(int nch) { return 2048 / nch < 128 ? 2048 / nch : 128; }
 constexpr int kTaskChunk = 32;                               // members summed by one wave task
 constexpr int kCsrWaves = 16;                                // waves of the CSR-building workgroup
 

@@ -7,9 +7,9 @@
 //   lists : per (sequence, kv head, layer) the pivots that may receive tokens are listed per
 //           token class (one class in a cross-modal layer, text / image in an intra-modal one),
 //           in ascending slot order, padded to a multiple of 32 with copies of the first entry;
-//           their K rows are packed next to each other in the order and swizzle the match
-//           kernel's LDS tiles use, and their 1/norm is tabulated.  Ineligible pivots are not
-//           in any list, so the contraction below never meets them.
+//           their K rows are packed next to each other with the row stride the match kernel's
+//           LDS tiles use (one 16-byte chunk of padding per row), and their 1/norm is tabulated.
+//           Ineligible pivots are not in any list, so the contraction below never meets them.
 //   match : a workgroup owns a tile of tokens of one class (32*KS per wave, held as MFMA B
 //           operands in registers straight from HBM) and walks over the class's pivot list in
 //           LDS tiles that arrive by direct global->LDS loads, double buffered.  The similarity
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void match_lists_kernel(Ctx c) {
   const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *pl_slot = c.pl_slot + lbase;
   float *pl_w = c.pl_w + lbase;
-  uint4 *pack = c.pack + lbase * NCH;
+  uint4 *pack = c.pack + lbase * (NCH + 1);
   const bool cross = c.mode[l * sh.batch + b] != 0;
 
   // ordered placement of the eligible slots of each class.  Every workgroup of the split writes
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void match_lists_kernel(Ctx c) {
       float ss = chunk_sumsq<BF16>(v);
 #pragma unroll
       for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      pack[(long long)(cls * Bp + e) * NCH + (ch ^ (e & (NCH - 1)))] = v;
+      pack[(long long)(cls * Bp + e) * (NCH + 1) + ch] = v;
       if (ch == 0) pl_w[cls * Bp + e] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
     }
   }
@@ -120,10 +120,12 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
   constexpr int NCH = CF::NCH, NF = CF::NF;
   constexpr int KS = match_subs(BF16);
   constexpr int TILE = kMatchWaves * 32 * KS;
-  constexpr int ROWS = kPivotTileBytes / (NCH * 16);  // list rows per LDS tile
+  constexpr int ROWS = match_tile_rows(NCH);  // list rows per LDS tile
+  constexpr int kMfmaPerBlock = KS * NF * (BF16 ? 1 : 4);
   extern __shared__ uint4 lds[];
-  uint4 *lds_rows = lds;                                             // [2][ROWS][NCH]
-  float *lds_w = reinterpret_cast<float *>(lds + 2 * ROWS * NCH);    // [2][ROWS]
+  constexpr int RS = NCH + 1;  // row stride in chunks: the odd stride keeps 16 rows' fragments on distinct banks
+  uint4 *lds_rows = lds;                                             // [2][ROWS][RS]
+  float *lds_w = reinterpret_cast<float *>(lds + 2 * ROWS * RS);     // [2][ROWS]
 
   const Shape &sh = c.sh;
   const int *meta = c.meta;
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
   int *assign = c.assign + unit * sh.T + s.tok_off;
   const int Bp = (s.B + 31) & ~31;
   const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b] + cls * Bp;
-  const uint4 *pack = c.pack + lbase * NCH;
+  const uint4 *pack = c.pack + lbase * RS;
   const float *pl_w = c.pl_w + lbase;
   const int npc = c.pl_n[(unit * sh.batch + b) * 2 + cls];  // list length, a multiple of 32
   const int ntiles = (npc + ROWS - 1) / ROWS;
@@ -169,11 +171,11 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
   auto stage = [&](int t, int buf) {
     const int r0 = t * ROWS;
     const int rows = min(ROWS, npc - r0);
-    const uint4 *src = pack + (long long)r0 * NCH;
-    uint4 *dst = lds_rows + buf * ROWS * NCH;
-    const int nchunks = rows * NCH;  // a multiple of 256
+    const uint4 *src = pack + (long long)r0 * RS;
+    uint4 *dst = lds_rows + buf * ROWS * RS;
+    const int nchunks = rows * RS;  // the tile is a plain copy of that part of the pack
     for (int q0 = wave * 64; q0 < nchunks; q0 += kThreads)
-      load_to_lds<16>(src + q0 + lane, dst + q0);
+      if (q0 + lane < nchunks) load_to_lds<16>(src + q0 + lane, dst + q0);
     if (wave * 64 + lane < rows)
       load_to_lds<4>(pl_w + r0 + wave * 64 + lane, lds_w + buf * ROWS + wave * 64);
   };
@@ -183,16 +185,14 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
   const int wv0 = v0 + wave * 32 * KS;
   const bool active = wv0 < cn;
   uint4 kf[KS][NF];
-  int tok[KS];
-  bool valid[KS];
   float shift[KS];
+  auto token_of = [&](int sub) {  // position of this lane's token of group sub (the class's last one past the end)
+    const int vc = min(wv0 + sub * 32 + n, cn - 1);
+    return cross ? vc : order[vc];
+  };
 #pragma unroll
   for (int sub = 0; sub < KS; ++sub) {
-    const int v = wv0 + sub * 32 + n;
-    valid[sub] = v < cn;
-    const int vc = min(v, cn - 1);
-    tok[sub] = cross ? vc : order[vc];
-    const uint4 *row = K + (long long)tok[sub] * sh.ks_tok + half;
+    const uint4 *row = K + (long long)token_of(sub) * sh.ks_tok + half;
 #pragma unroll
     for (int f = 0; f < NF; ++f) kf[sub][f] = row[2 * f];
   }
@@ -209,45 +209,65 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
 #pragma unroll
   for (int sub = 0; sub < KS; ++sub) { best[sub] = 0u; bblk[sub] = 0; }
 
+  // A block is 32 list rows against this wave's tokens: every fragment read from LDS feeds KS matrix
+  // instructions (one per token group), fragments are requested kAhead steps before they are used,
+  // then the KS x 16 dot products of each lane are folded into the running maxima.  The two waves
+  // that share a SIMD overlap one's matrix phase with the other's folding.
+  constexpr int NBLK = ROWS / 32;   // blocks per LDS tile
+  constexpr int kBlockBytes = 32 * RS * 16;
+  constexpr int kAhead = NF < 3 ? NF : 3;
+  const int fa = (n * RS + half) * 16;  // byte offset of this lane's first fragment inside a block
+  const char *lds_bytes = reinterpret_cast<const char *>(lds);
   for (int t = 0; t < ntiles; ++t) {
     __builtin_amdgcn_s_waitcnt(0);  // this wave's part of tile t has landed
     __syncthreads();                // ... and everybody else's; tile t-1 is no longer read
     if (t + 1 < ntiles) stage(t + 1, (t + 1) & 1);
     if (!active) continue;
-    const uint4 *rows = lds_rows + (t & 1) * ROWS * NCH;
-    const float *wt = lds_w + (t & 1) * ROWS;
+    const char *rows = lds_bytes + (t & 1) * (ROWS * RS * 16) + fa;
+    const char *wt = reinterpret_cast<const char *>(lds_w + (t & 1) * ROWS) + 16 * half;
     const int nblk = min(ROWS, npc - t * ROWS) >> 5;
-    for (int pb = 0; pb < nblk; ++pb) {
-      f32x16_t acc[KS];
+    uint4 pf[kAhead];  // the next fragments, requested ahead of their use (also across blocks of the tile)
 #pragma unroll
-      for (int sub = 0; sub < KS; ++sub)
+    for (int f = 0; f < kAhead; ++f) pf[f] = *reinterpret_cast<const uint4 *>(rows + 32 * f);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[sub][i] = 0.f;
-      const int r = pb * 32 + n;
-      const uint4 *prow = rows + r * NCH;
-      const int sw = r & (NCH - 1);
+    for (int pb = 0; pb < NBLK; ++pb) {
+      if (pb < nblk) {
+        const char *brow = rows + pb * kBlockBytes;
+        f32x16_t acc[KS];
 #pragma unroll
-      for (int f = 0; f < NF; ++f) {
-        const uint4 pf = prow[(2 * f + half) ^ sw];
+        for (int sub = 0; sub < KS; ++sub)
 #pragma unroll
-        for (int sub = 0; sub < KS; ++sub) mma_chunk<BF16>(acc[sub], pf, kf[sub][f]);  // [pivot][token]
-      }
-      float w[16];
+          for (int i = 0; i < 16; ++i) acc[sub][i] = 0.f;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 w4 = *reinterpret_cast<const float4 *>(wt + pb * 32 + 8 * g + 4 * half);
-        w[4 * g] = w4.x; w[4 * g + 1] = w4.y; w[4 * g + 2] = w4.z; w[4 * g + 3] = w4.w;
-      }
-      const int blk = t * (ROWS / 32) + pb;
+        for (int f = 0; f < NF; ++f) {
+          const uint4 cur = pf[f % kAhead];
+          if (f + kAhead < NF) pf[f % kAhead] = *reinterpret_cast<const uint4 *>(brow + 32 * (f + kAhead));
 #pragma unroll
-      for (int sub = 0; sub < KS; ++sub) {
-        unsigned p[16];
+          for (int sub = 0; sub < KS; ++sub) mma_chunk<BF16>(acc[sub], cur, kf[sub][f]);  // [pivot][token]
+        }
+        if (pb + 1 < nblk) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          p[i] = (__float_as_uint(fmaf(acc[sub][i], w[i], shift[sub])) & ~15u) | (unsigned)(15 - i);
+          for (int f = 0; f < kAhead; ++f)
+            pf[f] = *reinterpret_cast<const uint4 *>(brow + kBlockBytes + 32 * f);
+        }
+        float wv[16];  // 1/norm of this lane's 16 rows of the block
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) p[0] = max(max(p[0], p[i]), p[i + 1]);
-        if (p[0] > best[sub]) { best[sub] = p[0]; bblk[sub] = blk; }
+        for (int g = 0; g < 4; ++g) {
+          const float4 w4 = *reinterpret_cast<const float4 *>(wt + pb * 128 + 32 * g);
+          wv[4 * g] = w4.x; wv[4 * g + 1] = w4.y; wv[4 * g + 2] = w4.z; wv[4 * g + 3] = w4.w;
+        }
+        const int blk = t * NBLK + pb;
+#pragma unroll
+        for (int sub = 0; sub < KS; ++sub) {
+          unsigned m = 0u;
+#pragma unroll
+          for (int i = 0; i < 16; i += 2) {
+            const unsigned p0 = (__float_as_uint(fmaf(acc[sub][i], wv[i], shift[sub])) & ~15u) | (unsigned)(15 - i);
+            const unsigned p1 = (__float_as_uint(fmaf(acc[sub][i + 1], wv[i + 1], shift[sub])) & ~15u) | (unsigned)(14 - i);
+            m = max(max(m, p0), p1);
+          }
+          if (m > best[sub]) { best[sub] = m; bblk[sub] = blk; }
+        }
       }
     }
   }
@@ -262,9 +282,10 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
     const unsigned other = __shfl_xor(best[sub], 32, 64) >> 4;
     const int oe = __shfl_xor(e, 32, 64);
     if (other > mine || (other == mine && oe < e)) e = oe;
-    if (half == 0 && valid[sub] && assign[tok[sub]] == -2) {
+    const int tok = token_of(sub);
+    if (half == 0 && wv0 + sub * 32 + n < cn && assign[tok] == -2) {
       const int slot = npc > 0 ? pl_slot[e] : -1;
-      assign[tok[sub]] = slot;
+      assign[tok] = slot;
       dropped += slot < 0;
     }
   }
@@ -275,13 +296,13 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
 template <bool BF16, int D>
 hipError_t launch_match_t(const Ctx &c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
-  constexpr int ROWS = kPivotTileBytes / (NCH * 16);
+  constexpr int ROWS = match_tile_rows(NCH);
   const Shape &sh = c.sh;
   {
     ProfScope ps(c.stream, KID_MATCH_LISTS);
     match_lists_kernel<BF16, D><<<dim3(sh.batch * kListSplit, sh.Hkv, sh.n_layers), kThreads, 0, c.stream>>>(c);
   }
-  const size_t lds = 2 * (size_t)kPivotTileBytes + 2 * ROWS * sizeof(float);
+  const size_t lds = 2 * (size_t)ROWS * (NCH + 1) * 16 + 2 * ROWS * sizeof(float);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(match_kernel<BF16, D>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
