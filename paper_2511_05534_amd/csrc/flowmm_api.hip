@@ -80,7 +80,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   sh.qs_layer = p->q_stride_layer / epc; sh.qs_head = p->q_stride_head / epc; sh.qs_tok = p->q_stride_token / epc;
 
   const int batch = p->batch;
-  const int match_tile = match_tile_tokens(sh.bf16);
+  const int match_tile = match_tile_tokens(sh.bf16), score_tile = score_tile_keys(sh.bf16);
   std::vector<int32_t> cu_score(batch + 1, 0), cu_match(batch + 1, 0), cu_task(batch + 1, 0),
       cu_multi(batch + 1, 0), cu_part(batch + 1, 0), cu_bp(batch + 1, 0);
   std::vector<int32_t> seq((size_t)batch * SW_WORDS, 0);
@@ -109,7 +109,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     }
     if (pos != L) return fail(FLOWMM_EINVAL, "spans of sequence %d cover [0,%d), not [0,%d)", b, pos, L);
     const int E = L - B;
-    cu_score[b + 1] = cu_score[b] + (L + kScoreTile - 1) / kScoreTile;
+    cu_score[b + 1] = cu_score[b] + (L + score_tile - 1) / score_tile;
     // an intra-modal layer matches text and image tokens in separate tiles: one tile more at most
     cu_match[b + 1] = cu_match[b] + (L + match_tile - 1) / match_tile + 1;
     cu_bp[b + 1] = cu_bp[b] + (B + 31) / 32 * 32;
@@ -249,7 +249,7 @@ void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *w
   c.meta = reinterpret_cast<int *>(ws + lo.rg.meta);
   c.mod = reinterpret_cast<uint8_t *>(ws + lo.rg.mod);
   c.part_stats = reinterpret_cast<float2 *>(ws + lo.rg.part_stats);
-  c.rowstat = reinterpret_cast<float2 *>(ws + lo.rg.rowstat);
+  c.rowstat = reinterpret_cast<float *>(ws + lo.rg.rowstat);
   c.cross_part = reinterpret_cast<float *>(ws + lo.rg.cross_part);
   c.cls_order = reinterpret_cast<int *>(ws + lo.rg.cls_order);
   c.pl_slot = reinterpret_cast<int *>(ws + lo.rg.pl_slot);

@@ -24,7 +24,7 @@ struct Ctx {
   uint8_t *mod;        // [T]                             modality of every packed token
   int *cls_order;      // [T]                             per sequence: text positions ascending, then image positions
   float2 *part_stats;  // [Lyr][Hkv][tiles_score][R_pad]  (max, sum exp2) of each row over a tile
-  float2 *rowstat;     // [Lyr][Hkv][batch][R_pad]        (max, 1/sum) of each row
+  float *rowstat;      // [Lyr][Hkv][batch][R_pad]        max + log2(sum exp2) of each row, +inf for padding rows
   float *cross_part;   // [Lyr][Hq][tiles_score]          cross-modal mass of a head over a tile
   int *pl_slot;        // [Lyr][Hkv][2*SBP]               eligible pivots per (sequence, token class): their slots, ascending
   float *pl_w;         // [Lyr][Hkv][2*SBP]               1/norm of those pivots (0 for a zero row)

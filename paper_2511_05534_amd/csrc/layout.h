@@ -20,6 +20,7 @@ enum MetaWord {
   MW_OFF_CU_MULTI, // word offset of cu_multi[batch+1]   (upper bounds)
   MW_OFF_CU_PART,  // word offset of cu_part[batch+1]    (upper bounds)
   MW_OFF_CU_BP,    // word offset of cu_bp[batch+1]      (budgets rounded up to 32, prefix sums)
+  MW_ZERO16,       // four zero words (a 16-byte aligned chunk of zeros for padding loads)
   MW_HEADER = 16
 };
 
@@ -38,9 +39,10 @@ enum SeqWord {
 };
 
 // tiling constants shared by host sizing and kernels
-constexpr int kScoreKeysPerWave = 64;
 constexpr int kScoreWaves = 4;
-constexpr int kScoreTile = kScoreKeysPerWave * kScoreWaves;  // keys per workgroup
+// 32-key groups a wave of the score kernels holds in registers (its MFMA operands)
+constexpr int score_subs(bool bf16) { return bf16 ? 4 : 2; }
+constexpr int score_tile_keys(bool bf16) { return kScoreWaves * 32 * score_subs(bf16); }  // keys per workgroup
 constexpr int kMatchWaves = 4;
 // 32-token groups a wave of the match kernel holds in registers (its MFMA B operands)
 constexpr int match_subs(bool bf16) { return bf16 ? 4 : 2; }

@@ -5,9 +5,13 @@
 //
 // The logits tile of a workgroup never leaves registers.  Keys are split across workgroups,
 // so the softmax needs every row's global (max, sum): pass 1 writes those per tile, a small
-// pass 2 folds them per row, pass 3 recomputes the tile's logits and reduces the normalised
-// probabilities over the query rows.  Both heavy passes read K once, straight from HBM into
-// MFMA operand registers (one 16-byte chunk per lane and k step).
+// pass 2 folds them per row into one offset c = max + log2(sum), pass 3 recomputes the tile's
+// logits and reduces exp2(logit - c) over the query rows.  Both heavy passes read K once,
+// straight from HBM into MFMA operand registers (one 16-byte chunk per lane and k step, 32*KS
+// keys per wave); the query rows of the (sequence, kv head, layer) arrive in LDS by direct
+// global->LDS loads and every fragment read from there feeds KS matrix instructions.
+// Only the tiles that reach into the window (or past the end of the sequence) pay for the
+// causal mask; only sequences whose window holds image tokens pay for per-row modality weights.
 #include "device_common.h"
 #include "kernels.h"
 #include "profile.h"
@@ -17,58 +21,80 @@ namespace flowmm {
 namespace {
 
 constexpr int kThreads = kScoreWaves * 64;
-constexpr int kSub = kScoreKeysPerWave / 32;
 
 struct TileCtx {
   int b, tile, x, gkv, l, wave, lane, n, half, key0;  // key0: first key of this wave
+  bool masked;                                        // some key of the tile is hidden from some window row
   SeqInfo s;
 };
 
-__device__ __forceinline__ TileCtx tile_ctx(const Ctx &c) {
-  TileCtx t;
+// Workgroups are handed to the eight XCDs in turn; all key tiles of a (layer, kv head) go to one
+// XCD so that its query rows sit in one L2.  Returns false for the padding workgroups.
+template <int TILE>
+__device__ __forceinline__ bool tile_ctx(const Ctx &c, TileCtx &t) {
+  const Shape &sh = c.sh;
   const int *meta = c.meta;
-  const int batch = meta[MW_BATCH];
+  const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+  const int ul = k / sh.tiles_score;
+  t.x = k - ul * sh.tiles_score;
+  const int unit = ul * 8 + xcd;
+  if (unit >= sh.n_layers * sh.Hkv) return false;
+  t.l = unit / sh.Hkv;
+  t.gkv = unit - t.l * sh.Hkv;
   const int *cu = meta + meta[MW_OFF_CU_SCORE];
-  t.x = blockIdx.x;
-  t.b = find_seq(cu, batch, t.x);
+  t.b = find_seq(cu, meta[MW_BATCH], t.x);
   t.tile = t.x - cu[t.b];
-  t.gkv = blockIdx.y;
-  t.l = blockIdx.z;
   t.s = load_seq(meta, t.b);
   t.wave = threadIdx.x >> 6;
   t.lane = threadIdx.x & 63;
   t.n = t.lane & 31;
   t.half = t.lane >> 5;
-  t.key0 = t.tile * kScoreTile + t.wave * kScoreKeysPerWave;
-  return t;
+  t.key0 = t.tile * TILE + t.wave * (TILE / kScoreWaves);
+  t.masked = (t.tile + 1) * TILE > t.s.L - sh.W;
+  return true;
 }
 
-// Stage the R_pad query rows of this (sequence, layer, kv head) into LDS, row stride NCH+1
+// lane i of the wave fetches 16 bytes from its own global address; they land at lds_base + 16 i
+// (lds_base wave-uniform).  Inline assembly, so the compiler does not wait for it before unrelated
+// LDS traffic (nothing else here uses M0); the caller waits with s_waitcnt vmcnt(0) and a barrier.
+typedef __attribute__((address_space(3))) void lds_void;
+__device__ __forceinline__ void load16_to_lds(const void *gptr, void *lds_base) {
+  const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+// Request the R_pad query rows of this (sequence, layer, kv head) into LDS, row stride NCH+1
 // chunks (the odd stride keeps the 16-byte fragment reads of 16 consecutive rows on distinct
-// banks).  Rows beyond W inside a head's padded block are zero.
+// banks).  Rows beyond W inside a head's padded block, and the padding chunk of every row, come
+// from 16 zero bytes in the metadata block.
 template <bool BF16, int D>
 __device__ __forceinline__ void stage_queries(const Ctx &c, const TileCtx &t, uint4 *ldsq) {
-  constexpr int NCH = Cfg<BF16, D>::NCH;
+  constexpr int NCH = Cfg<BF16, D>::NCH, RS = NCH + 1;
   const Shape &sh = c.sh;
   const uint4 *Q = reinterpret_cast<const uint4 *>(c.Q) + (long long)t.l * sh.qs_layer;
-  for (int idx = threadIdx.x; idx < sh.R_pad * NCH; idx += kThreads) {
-    const int row = idx / NCH, ch = idx - row * NCH;
-    const int g = row / sh.W_pad, r = row - g * sh.W_pad;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < sh.W)
-      v = Q[(long long)(t.gkv * sh.G + g) * sh.qs_head + (long long)(t.b * sh.W + r) * sh.qs_tok + ch];
-    ldsq[row * (NCH + 1) + ch] = v;
+  const uint4 *zero = reinterpret_cast<const uint4 *>(c.meta + MW_ZERO16);
+  const int total = sh.R_pad * RS;
+  for (int q0 = t.wave * 64; q0 < total; q0 += kThreads) {
+    const int q = q0 + t.lane;
+    if (q < total) {
+      const int row = q / RS, ch = q - row * RS;
+      const int g = row / sh.W_pad, r = row - g * sh.W_pad;
+      const uint4 *src = zero;
+      if (r < sh.W && ch < NCH)
+        src = Q + (long long)(t.gkv * sh.G + g) * sh.qs_head + (long long)(t.b * sh.W + r) * sh.qs_tok + ch;
+      load16_to_lds(src, ldsq + q0);
+    }
   }
 }
 
-template <bool BF16, int D>
-__device__ __forceinline__ void load_keys(const Ctx &c, const TileCtx &t, uint4 (&kf)[kSub][Cfg<BF16, D>::NF]) {
+template <bool BF16, int D, int KS>
+__device__ __forceinline__ void load_keys(const Ctx &c, const TileCtx &t, uint4 (&kf)[KS][Cfg<BF16, D>::NF]) {
   constexpr int NF = Cfg<BF16, D>::NF;
   const Shape &sh = c.sh;
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)t.l * sh.ks_layer +
                    (long long)t.gkv * sh.ks_head;
 #pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) {
+  for (int sub = 0; sub < KS; ++sub) {
     int key = t.key0 + sub * 32 + t.n;
     key = key < t.s.L ? key : t.s.L - 1;
     const uint4 *row = K + (long long)(t.s.tok_off + key) * sh.ks_tok + t.half;
@@ -77,59 +103,107 @@ __device__ __forceinline__ void load_keys(const Ctx &c, const TileCtx &t, uint4 
   }
 }
 
+// The products of one block of 32 query rows with this wave's keys.  KEYS_AS_ROWS: accumulator
+// rows are keys and lane n owns query row n (pass 1); otherwise rows are query rows and lane n owns
+// key n of every group (pass 3).  Fragments are requested kAhead steps ahead, also across blocks.
+template <bool BF16, int D, int KS, bool KEYS_AS_ROWS, int AHEAD>
+__device__ __forceinline__ void block_products(f32x16_t (&acc)[KS], const uint4 (&kf)[KS][Cfg<BF16, D>::NF],
+                                               uint4 (&pf)[AHEAD], const char *qrow, bool more) {
+  constexpr int NF = Cfg<BF16, D>::NF, RS = Cfg<BF16, D>::NCH + 1;
+#pragma unroll
+  for (int sub = 0; sub < KS; ++sub)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[sub][i] = 0.f;
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    const uint4 cur = pf[f % AHEAD];
+    if (f + AHEAD < NF) pf[f % AHEAD] = *reinterpret_cast<const uint4 *>(qrow + 32 * (f + AHEAD));
+#pragma unroll
+    for (int sub = 0; sub < KS; ++sub) {
+      if constexpr (KEYS_AS_ROWS) mma_chunk<BF16>(acc[sub], kf[sub][f], cur);
+      else mma_chunk<BF16>(acc[sub], cur, kf[sub][f]);
+    }
+  }
+  if (more) {
+#pragma unroll
+    for (int f = 0; f < AHEAD; ++f) pf[f] = *reinterpret_cast<const uint4 *>(qrow + 32 * RS * 16 + 32 * f);
+  }
+}
+
 // ---- pass 1: per-tile row statistics ---------------------------------------------------
-template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads) void score_stats_kernel(Ctx c) {
-  constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF;
-  extern __shared__ uint4 lds[];
+template <bool BF16, int D, int KS, bool MASKED>
+__device__ __forceinline__ void stats_body(const Ctx &c, const TileCtx &t, const uint4 (&kf)[KS][Cfg<BF16, D>::NF],
+                                           const uint4 *ldsq, float2 *lds_stats) {
+  constexpr int NF = Cfg<BF16, D>::NF, RS = Cfg<BF16, D>::NCH + 1;
+  constexpr int AHEAD = NF < 3 ? NF : 3;
   const Shape &sh = c.sh;
-  const TileCtx t = tile_ctx(c);
-  uint4 *ldsq = lds;
-  float2 *lds_stats = reinterpret_cast<float2 *>(lds + sh.R_pad * (NCH + 1));  // [waves][R_pad]
-
-  uint4 kf[kSub][NF];
-  load_keys<BF16, D>(c, t, kf);
-  stage_queries<BF16, D>(c, t, ldsq);
-  __syncthreads();
-
   const int RB = sh.R_pad >> 5;
   const float cl = sh.scale_log2e;
+  const char *qbase = reinterpret_cast<const char *>(ldsq) + (t.n * RS + t.half) * 16;
+  uint4 pf[AHEAD];
+#pragma unroll
+  for (int f = 0; f < AHEAD; ++f) pf[f] = *reinterpret_cast<const uint4 *>(qbase + 32 * f);
   for (int rb = 0; rb < RB; ++rb) {
-    f32x16_t acc[kSub];
-#pragma unroll
-    for (int sub = 0; sub < kSub; ++sub)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[sub][i] = 0.f;
-    const uint4 *qrow = ldsq + (rb * 32 + t.n) * (NCH + 1) + t.half;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      const uint4 qf = qrow[2 * f];
-#pragma unroll
-      for (int sub = 0; sub < kSub; ++sub) mma_chunk<BF16>(acc[sub], kf[sub][f], qf);  // [key][query row]
-    }
+    f32x16_t acc[KS];
+    block_products<BF16, D, KS, true, AHEAD>(acc, kf, pf, qbase + rb * (32 * RS * 16), rb + 1 < RB);  // [key][query row]
     const int row = rb * 32 + t.n;
-    const int r = row % sh.W_pad;
-    const int limit = r < sh.W ? t.s.L - sh.W + r : -1;  // last key this query may see
-    float m = -INFINITY;
+    float m = -INFINITY, z = 0.f;
+    if constexpr (MASKED) {
+      const int r = row % sh.W_pad;
+      const int limit = r < sh.W ? t.s.L - sh.W + r : -1;  // last key this query may see
 #pragma unroll
-    for (int sub = 0; sub < kSub; ++sub)
+      for (int sub = 0; sub < KS; ++sub)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = t.key0 + sub * 32 + acc_row(i, t.half);
-        const float v = key <= limit ? acc[sub][i] * cl : -INFINITY;
-        acc[sub][i] = v;
-        m = fmaxf(m, v);
+        for (int i = 0; i < 16; ++i) {
+          const int key = t.key0 + sub * 32 + acc_row(i, t.half);
+          acc[sub][i] = key <= limit ? acc[sub][i] : -INFINITY;
+          m = fmaxf(m, acc[sub][i]);
+        }
+      if (m > -INFINITY) {
+        const float mc = m * cl;
+#pragma unroll
+        for (int sub = 0; sub < KS; ++sub)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) z += fast_exp2(fmaf(acc[sub][i], cl, -mc));
       }
-    float z = 0.f;
-    if (m > -INFINITY) {
+      m *= cl;
+    } else {
 #pragma unroll
-      for (int sub = 0; sub < kSub; ++sub)
+      for (int sub = 0; sub < KS; ++sub)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) z += fast_exp2(acc[sub][i] - m);
+        for (int i = 0; i < 16; i += 2) m = fmaxf(fmaxf(m, acc[sub][i]), acc[sub][i + 1]);
+      m *= cl;  // cl > 0: the largest logit is the largest product
+#pragma unroll
+      for (int sub = 0; sub < KS; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) z += fast_exp2(fmaf(acc[sub][i], cl, -m));
     }
     const float m2 = __shfl_xor(m, 32, 64), z2 = __shfl_xor(z, 32, 64);
     stat_combine(m, z, m2, z2);
     if (t.half == 0) lds_stats[t.wave * sh.R_pad + row] = make_float2(m, z);
+  }
+}
+
+template <bool BF16, int D>
+__global__ __launch_bounds__(kThreads, 2) void score_stats_kernel(Ctx c) {
+  constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF, KS = score_subs(BF16);
+  extern __shared__ uint4 lds[];
+  const Shape &sh = c.sh;
+  TileCtx t;
+  if (!tile_ctx<score_tile_keys(BF16)>(c, t)) return;
+  uint4 *ldsq = lds;
+  float2 *lds_stats = reinterpret_cast<float2 *>(lds + sh.R_pad * (NCH + 1));  // [waves][R_pad]
+
+  stage_queries<BF16, D>(c, t, ldsq);
+  uint4 kf[KS][NF];
+  load_keys<BF16, D, KS>(c, t, kf);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (t.key0 < t.s.L) {  // waves past the end of the sequence have nothing to add
+    if (t.masked) stats_body<BF16, D, KS, true>(c, t, kf, ldsq, lds_stats);
+    else stats_body<BF16, D, KS, false>(c, t, kf, ldsq, lds_stats);
+  } else {
+    for (int row = t.lane; row < sh.R_pad; row += 64) lds_stats[t.wave * sh.R_pad + row] = make_float2(-INFINITY, 0.f);
   }
   __syncthreads();
   float2 *out = c.part_stats + ((long long)(t.l * sh.Hkv + t.gkv) * sh.tiles_score + t.x) * sh.R_pad;
@@ -151,102 +225,129 @@ __global__ __launch_bounds__(256) void score_combine_kernel(Ctx c) {
   const int *cu = c.meta + c.meta[MW_OFF_CU_SCORE];
   const int x0 = cu[b], x1 = cu[b + 1];
   const float2 *in = c.part_stats + (long long)(l * sh.Hkv + gkv) * sh.tiles_score * sh.R_pad;
-  float2 *out = c.rowstat + ((long long)(l * sh.Hkv + gkv) * sh.batch + b) * sh.R_pad;
+  float *out = c.rowstat + ((long long)(l * sh.Hkv + gkv) * sh.batch + b) * sh.R_pad;
   for (int row = threadIdx.x; row < sh.R_pad; row += 256) {
     float m = -INFINITY, z = 0.f;
-    for (int x = x0; x < x1; ++x) {
-      const float2 o = in[(long long)x * sh.R_pad + row];
-      stat_combine(m, z, o.x, o.y);
+    if (row % sh.W_pad < sh.W) {
+      for (int x = x0; x < x1; ++x) {
+        const float2 o = in[(long long)x * sh.R_pad + row];
+        stat_combine(m, z, o.x, o.y);
+      }
     }
-    out[row] = z > 0.f ? make_float2(m, 1.0f / z) : make_float2(0.f, 0.f);
+    // exp2(logit - c) is the normalised probability; padding rows get c = +inf, probability 0
+    out[row] = z > 0.f ? m + __builtin_amdgcn_logf(z) : INFINITY;
   }
 }
 
 // ---- pass 3: normalised probabilities reduced over the query rows ------------------------
-template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads) void score_colsum_kernel(Ctx c) {
-  constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF;
-  extern __shared__ uint4 lds[];
+template <bool BF16, int D, int KS, bool MASKED, bool WIN_IMG>
+__device__ __forceinline__ void colsum_body(const Ctx &c, const TileCtx &t, const uint4 (&kf)[KS][Cfg<BF16, D>::NF],
+                                            const int (&keymod)[KS], const uint4 *ldsq, const float *lds_c,
+                                            const float *lds_rowimg, float *lds_cross, float (&colsum)[KS]) {
+  constexpr int NF = Cfg<BF16, D>::NF, RS = Cfg<BF16, D>::NCH + 1;
+  constexpr int AHEAD = NF < 3 ? NF : 3;
   const Shape &sh = c.sh;
-  const TileCtx t = tile_ctx(c);
-  uint4 *ldsq = lds;
-  float2 *lds_rs = reinterpret_cast<float2 *>(lds + sh.R_pad * (NCH + 1));  // [R_pad]
-  float *lds_rowimg = reinterpret_cast<float *>(lds_rs + sh.R_pad);          // [W_pad]
-  float *lds_cross = lds_rowimg + sh.W_pad;                                  // [waves][G]
-
-  uint4 kf[kSub][NF];
-  load_keys<BF16, D>(c, t, kf);
-  stage_queries<BF16, D>(c, t, ldsq);
-  const float2 *rs = c.rowstat + ((long long)(t.l * sh.Hkv + t.gkv) * sh.batch + t.b) * sh.R_pad;
-  for (int row = threadIdx.x; row < sh.R_pad; row += kThreads) lds_rs[row] = rs[row];
-  const uint8_t *mod = c.mod + t.s.tok_off;
-  for (int r = threadIdx.x; r < sh.W_pad; r += kThreads)
-    lds_rowimg[r] = (r < sh.W && mod[t.s.L - sh.W + r]) ? 1.f : 0.f;
-  int keymod[kSub], key[kSub];
-#pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) {
-    key[sub] = t.key0 + sub * 32 + t.n;
-    keymod[sub] = mod[key[sub] < t.s.L ? key[sub] : t.s.L - 1];
-  }
-  __syncthreads();
-
   const int RB = sh.R_pad >> 5;
-  const int blocks_per_head = sh.W_pad >> 5;
+  const int bph = sh.W_pad >> 5;  // row blocks per query head
   const float cl = sh.scale_log2e;
-  const bool win_img = t.s.win_has_img != 0;
-  float colsum[kSub], cross_acc = 0.f;
+  const char *qbase = reinterpret_cast<const char *>(ldsq) + (t.n * RS + t.half) * 16;
+  uint4 pf[AHEAD];
 #pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) colsum[sub] = 0.f;
-
+  for (int f = 0; f < AHEAD; ++f) pf[f] = *reinterpret_cast<const uint4 *>(qbase + 32 * f);
+  float cross_acc = 0.f;
+  int rbh = 0;  // row block inside the head
   for (int rb = 0; rb < RB; ++rb) {
-    f32x16_t acc[kSub];
+    f32x16_t acc[KS];
+    block_products<BF16, D, KS, false, AHEAD>(acc, kf, pf, qbase + rb * (32 * RS * 16), rb + 1 < RB);  // [query row][key]
+    float cr[16], wimg[16];
 #pragma unroll
-    for (int sub = 0; sub < kSub; ++sub)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[sub][i] = 0.f;
-    const uint4 *qrow = ldsq + (rb * 32 + t.n) * (NCH + 1) + t.half;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      const uint4 qf = qrow[2 * f];
-#pragma unroll
-      for (int sub = 0; sub < kSub; ++sub) mma_chunk<BF16>(acc[sub], qf, kf[sub][f]);  // [query row][key]
-    }
-    const int rbase = (rb % blocks_per_head) * 32;  // first window row of this block
-    float bs[kSub], bsi[kSub];
-#pragma unroll
-    for (int sub = 0; sub < kSub; ++sub) bs[sub] = bsi[sub] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int ri = acc_row(i, t.half);
-      const float2 st = lds_rs[rb * 32 + ri];           // (max, 1/sum); (0, 0) for padding rows
-      const int r = rbase + ri;
-      const int limit = r < sh.W ? t.s.L - sh.W + r : -1;
-      const float wimg = win_img ? lds_rowimg[r] : 0.f;
-#pragma unroll
-      for (int sub = 0; sub < kSub; ++sub) {
-        const float p = key[sub] <= limit ? fast_exp2(acc[sub][i] * cl - st.x) * st.y : 0.f;
-        bs[sub] += p;
-        bsi[sub] = fmaf(p, wimg, bsi[sub]);
+    for (int g = 0; g < 4; ++g) {
+      const float4 c4 = *reinterpret_cast<const float4 *>(lds_c + rb * 32 + 8 * g + 4 * t.half);
+      cr[4 * g] = c4.x; cr[4 * g + 1] = c4.y; cr[4 * g + 2] = c4.z; cr[4 * g + 3] = c4.w;
+      if constexpr (WIN_IMG) {
+        const float4 w4 = *reinterpret_cast<const float4 *>(lds_rowimg + rbh * 32 + 8 * g + 4 * t.half);
+        wimg[4 * g] = w4.x; wimg[4 * g + 1] = w4.y; wimg[4 * g + 2] = w4.z; wimg[4 * g + 3] = w4.w;
       }
     }
 #pragma unroll
-    for (int sub = 0; sub < kSub; ++sub) {
-      colsum[sub] += bs[sub];
+    for (int sub = 0; sub < KS; ++sub) {
+      const int key = t.key0 + sub * 32 + t.n;
+      float bs = 0.f, bsi = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float p = fast_exp2(fmaf(acc[sub][i], cl, -cr[i]));
+        if constexpr (MASKED) {
+          // window row r sees keys up to L - W + r; padding rows already have probability 0
+          const int r = rbh * 32 + acc_row(i, t.half);
+          p = key <= t.s.L - sh.W + r ? p : 0.f;
+        }
+        bs += p;
+        if constexpr (WIN_IMG) bsi = fmaf(p, wimg[i], bsi);
+      }
+      colsum[sub] += bs;
       // mass sent to the other modality: image keys seen by text rows, text keys by image rows
-      cross_acc += keymod[sub] ? bs[sub] - bsi[sub] : bsi[sub];
+      if constexpr (WIN_IMG) cross_acc += keymod[sub] ? bs - bsi : bsi;
+      else cross_acc += keymod[sub] ? bs : 0.f;
     }
-    if ((rb + 1) % blocks_per_head == 0) {
+    if (++rbh == bph) {
+      rbh = 0;
       const float v = wave_sum(cross_acc);
-      if (t.lane == 0) lds_cross[t.wave * sh.G + rb / blocks_per_head] = v;
+      if (t.lane == 0) lds_cross[t.wave * sh.G + rb / bph] = v;
       cross_acc = 0.f;
+    }
+  }
+}
+
+template <bool BF16, int D>
+__global__ __launch_bounds__(kThreads, 2) void score_colsum_kernel(Ctx c) {
+  constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF, KS = score_subs(BF16);
+  extern __shared__ uint4 lds[];
+  const Shape &sh = c.sh;
+  TileCtx t;
+  if (!tile_ctx<score_tile_keys(BF16)>(c, t)) return;
+  uint4 *ldsq = lds;
+  float *lds_c = reinterpret_cast<float *>(lds + sh.R_pad * (NCH + 1));  // [R_pad]
+  float *lds_rowimg = lds_c + sh.R_pad;                                  // [W_pad]
+  float *lds_cross = lds_rowimg + sh.W_pad;                              // [waves][G]
+
+  stage_queries<BF16, D>(c, t, ldsq);
+  uint4 kf[KS][NF];
+  load_keys<BF16, D, KS>(c, t, kf);
+  const float *rs = c.rowstat + ((long long)(t.l * sh.Hkv + t.gkv) * sh.batch + t.b) * sh.R_pad;
+  for (int row = threadIdx.x; row < sh.R_pad; row += kThreads) lds_c[row] = rs[row];
+  const uint8_t *mod = c.mod + t.s.tok_off;
+  for (int r = threadIdx.x; r < sh.W_pad; r += kThreads)
+    lds_rowimg[r] = (r < sh.W && mod[t.s.L - sh.W + r]) ? 1.f : 0.f;
+  for (int i = threadIdx.x; i < kScoreWaves * sh.G; i += kThreads) lds_cross[i] = 0.f;
+  int keymod[KS];
+#pragma unroll
+  for (int sub = 0; sub < KS; ++sub) {
+    const int key = t.key0 + sub * 32 + t.n;
+    keymod[sub] = mod[key < t.s.L ? key : t.s.L - 1];
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  float colsum[KS];
+#pragma unroll
+  for (int sub = 0; sub < KS; ++sub) colsum[sub] = 0.f;
+  if (t.key0 < t.s.L) {
+    const bool win_img = t.s.win_has_img != 0;
+    if (t.masked) {
+      if (win_img) colsum_body<BF16, D, KS, true, true>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
+      else colsum_body<BF16, D, KS, true, false>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
+    } else {
+      if (win_img) colsum_body<BF16, D, KS, false, true>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
+      else colsum_body<BF16, D, KS, false, false>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
     }
   }
   const float inv_rows = 1.0f / (float)(sh.G * sh.W);
   float *imp = c.importance + (long long)(t.l * sh.Hkv + t.gkv) * sh.T + t.s.tok_off;
 #pragma unroll
-  for (int sub = 0; sub < kSub; ++sub) {
+  for (int sub = 0; sub < KS; ++sub) {
+    const int key = t.key0 + sub * 32 + t.n;
     const float tot = colsum[sub] + __shfl_xor(colsum[sub], 32, 64);
-    if (t.half == 0 && key[sub] < t.s.L) imp[key[sub]] = tot * inv_rows;
+    if (t.half == 0 && key < t.s.L) imp[key] = tot * inv_rows;
   }
   __syncthreads();
   for (int g = threadIdx.x; g < sh.G; g += kThreads) {
@@ -263,8 +364,7 @@ hipError_t launch_score_t(const Ctx &c) {
   const Shape &sh = c.sh;
   const size_t q_bytes = (size_t)sh.R_pad * (NCH + 1) * 16;
   const size_t lds1 = q_bytes + (size_t)kScoreWaves * sh.R_pad * sizeof(float2);
-  const size_t lds3 = q_bytes + (size_t)sh.R_pad * sizeof(float2) + (size_t)sh.W_pad * 4 +
-                      (size_t)kScoreWaves * sh.G * 4;
+  const size_t lds3 = q_bytes + (size_t)sh.R_pad * 4 + (size_t)sh.W_pad * 4 + (size_t)kScoreWaves * sh.G * 4;
   hipError_t e;
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_stats_kernel<BF16, D>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
@@ -272,10 +372,12 @@ hipError_t launch_score_t(const Ctx &c) {
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_colsum_kernel<BF16, D>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3);
   if (e != hipSuccess) return e;
-  const dim3 grid(sh.tiles_score, sh.Hkv, sh.n_layers);
+  const int units = sh.n_layers * sh.Hkv;
+  const long long grid = (long long)((units + 7) / 8) * 8 * sh.tiles_score;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
   {
     ProfScope ps(c.stream, KID_SCORE_STATS);
-    score_stats_kernel<BF16, D><<<grid, kThreads, lds1, c.stream>>>(c);
+    score_stats_kernel<BF16, D><<<dim3((unsigned)grid), kThreads, lds1, c.stream>>>(c);
   }
   {
     ProfScope ps(c.stream, KID_SCORE_COMBINE);
@@ -283,7 +385,7 @@ hipError_t launch_score_t(const Ctx &c) {
   }
   {
     ProfScope ps(c.stream, KID_SCORE_COLSUM);
-    score_colsum_kernel<BF16, D><<<grid, kThreads, lds3, c.stream>>>(c);
+    score_colsum_kernel<BF16, D><<<dim3((unsigned)grid), kThreads, lds3, c.stream>>>(c);
   }
   return hipGetLastError();
 }
