@@ -31,7 +31,7 @@ def algorithmic_bytes(wl):
     d, G, W = wl.head_dim, wl.group, wl.window
     units = wl.n_layers * wl.n_kv_heads
     tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match", "merge_tasks", "select",
-                          "merge_csr", "unit_score", "unit_match", "unit_merge")}
+                          "merge_csr", "unit_plan", "unit_match", "unit_merge")}
     for L, B in zip(wl.seqlens, wl.budgets):
         row = d * s
         tot["whole_pass"] += units * (3 * L * row + 2 * B * row + G * W * row + 12 * L)
@@ -42,7 +42,7 @@ def algorithmic_bytes(wl):
         tot["merge_csr"] += units * (4 * L + 4 * (L - B))                  # assign in, member list out
         tot["merge_tasks"] += units * (2 * L * row + 2 * B * row + 4 * (L - B))  # K and V rows in, compacted out
         # unit-resident kernels (short prompts)
-        tot["unit_score"] += units * (L * row + G * W * row + 4 * L)       # K once, Q, importance out
+        tot["unit_plan"] += units * (L * row + G * W * row + 4 * L)       # K once, Q, importance out
         tot["unit_match"] += units * (L * row + 4 * L + 4 * L + 4 * B)     # K once, importance in, assign + kept out
         tot["unit_merge"] += units * (2 * L * row + 2 * B * row + 4 * L + 4 * B)  # K, V rows, assign, kept in; compacted out
     return tot

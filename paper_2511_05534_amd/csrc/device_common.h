@@ -146,7 +146,7 @@ __device__ __forceinline__ SeqInfo inline_seq(const InlineMeta &m, int b) {
   s.B = m.B[b];
   s.kept_off = m.kept_off[b];
   s.tau = m.tau[b];
-  s.win_has_img = 0;  // unused by the kernels that take inline metadata
+  s.win_has_img = (m.win_has_img >> b) & 1u;
   s.n_text = 0;
   return s;
 }

@@ -140,6 +140,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
       m.tok_off[b] = r[SW_TOK_OFF]; m.L[b] = r[SW_L]; m.B[b] = r[SW_B]; m.kept_off[b] = r[SW_KEPT_OFF];
       m.tau[b] = p->tau[b];
       m.span_off[b] = p->cu_spans[b];
+      if (r[SW_WIN_HAS_IMG]) m.win_has_img |= 1u << b;
     }
     m.span_off[batch] = n_spans;
     for (int j = 0; j < n_spans; ++j) {

@@ -73,6 +73,7 @@ struct InlineMeta {
   int span_off[kInlineSeqs + 1];  // spans of sequence b: [span_off[b], span_off[b+1])
   int span_end[kInlineSpans];     // exclusive end of each span, position local to its sequence
   unsigned span_is_image;         // bit j: span j holds image tokens
+  unsigned win_has_img;           // bit b: some proxy token of sequence b is an image token
 };
 
 // byte offsets into the workspace (all multiples of 256)

@@ -228,7 +228,7 @@ __device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], i
         const unsigned long long am = __ballot(act);
         if (am) {  // a whole wave on one digit is the common case for the exponent byte
           const int first = __ffsll((long long)am) - 1;
-          const int d0 = __shfl(dg, first, 64);
+          const int d0 = __builtin_amdgcn_readlane(dg, first);
           if (__ballot(act && dg == d0) == am) {
             if (lane == first) atomicAdd(&hist[d0], __popcll(am));
           } else if (act) {
@@ -254,8 +254,8 @@ __device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], i
       }
       const unsigned long long found = __ballot(digit >= 0);
       const int src = __ffsll((long long)found) - 1;
-      digit = __shfl(digit, src, 64);
-      remaining = __shfl(rem_new, src, 64);
+      digit = __builtin_amdgcn_readlane(digit, src);
+      remaining = __builtin_amdgcn_readlane(rem_new, src);
       prefix |= (unsigned)digit << shift;
       mask |= 255u << shift;
     }
@@ -273,8 +273,14 @@ __device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], i
     gt4 += gtj[j];
     eq4 += eqj[j];
   }
-  int total;
-  const int before = block_exclusive_scan<THREADS, int>(gt4 | (eq4 << 16), sc.wave_sums, &total);
+  // block-wide exclusive scan of the packed counts: a wave scan on the DPP path, then the totals of
+  // the earlier waves (one barrier)
+  const int packed = gt4 | (eq4 << 16);
+  const int inc = wave_inclusive_scan(packed);
+  if (lane == 63) sc.wave_sums[threadIdx.x >> 6] = inc;
+  __syncthreads();
+  int before = inc - packed;
+  for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += sc.wave_sums[w];
   int gt_before = before & 0xffff, eq_before = before >> 16;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {

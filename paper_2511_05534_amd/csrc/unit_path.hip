@@ -1,13 +1,15 @@
 // Unit-resident path for short prompts (bf16, every L <= 1024, G*W_pad <= 64, every B <= 256,
 // at most 8 sequences and 32 modality spans, whose description rides in the kernel arguments).
 //
-// When one (sequence, layer, kv head) unit fits on a compute unit, the whole logits tile
-// (G*W rows x L keys) stays in MFMA accumulator registers, so the softmax needs no second pass
-// over K and no partial statistics in HBM, and every step of a unit runs inside one workgroup:
-//   unit_score        : proxy attention -> importance   (K read once)
-//   unit_match        : flow + top-B split + cosine argmax (K read once, pivots staged once)
-//   unit_merge        : counting sort + segment sums    (K and V read once)
-// Three launches instead of ten.  The arithmetic is the same as in the generic kernels
+// When one (sequence, layer, kv head) unit fits on a compute unit, every step of a unit runs inside
+// one workgroup and nothing but K, V and the results touches HBM:
+//   unit_plan   : proxy attention -> importance, top-B split, cosine argmax as a cross-modal layer
+//                 does; the unit's keys stay in registers throughout (K read once)
+//   unit_match  : the layer's flow ratio and strategy (needs all its query heads, hence its own
+//                 launch); units of intra-modal layers are split and matched again with the
+//                 modality restriction, the others return at once
+//   unit_merge  : counting sort + segment sums    (K and V read once)
+// Three launches instead of eleven.  The arithmetic is the same as in the generic kernels
 // (score.hip, select.hip, match.hip, merge.hip); see those files for the paper passages.
 #include "device_common.h"
 #include "kernels.h"
@@ -33,201 +35,364 @@ static __device__ unsigned long long *g_trace;
 #define TRACE(k)
 #endif
 
-// ============================ score ==========================================================
-constexpr int kF1Threads = 512;
-constexpr int kF1Waves = kF1Threads / 64;
+// ============================ score + select + match (cross-modal) ===========================
+// One workgroup of eight waves per unit.  Wave w keeps the key tiles w, w+8, ... (32 keys each) in
+// registers for the whole kernel, in the layout every contraction here uses, so K is read from
+// HBM once.  The logits are computed twice from those registers: once for the row statistics,
+// once for the normalised column sums.  The pivots' rows go from the registers of the lanes that
+// hold them to LDS, and the same registers are the token operands of the cosine contraction.
+// Every fragment read from LDS (query rows, pivot rows) feeds one matrix instruction per tile of
+// the wave.  The layer's strategy needs all its query heads and is not known here: this kernel
+// matches as a cross-modal layer does; unit_match_kernel then settles the strategy and redoes the
+// intra-modal layers.
+constexpr int kPThreads = 512;
+constexpr int kPWaves = kPThreads / 64;
+
+struct PlanLds {  // byte offsets into the dynamic LDS block
+  int q, stat, cval, rowimg, cross, keys, assign, kept, piv, w, bias, total_bytes;
+};
+
+__host__ __device__ inline PlanLds plan_lds_layout(int rows, int b_pad, int nch) {
+  PlanLds m;
+  int off = 0;
+  m.q = off; off += rows * (nch + 1) * 16;
+  m.piv = off; off += b_pad * (nch + 1) * 16;
+  m.stat = off; off += kPWaves * rows * 8;
+  m.cval = off; off += rows * 4;
+  m.rowimg = off; off += rows * 4;
+  m.cross = off; off += 32 * 2 * 4;
+  m.keys = off; off += 1024 * 4;
+  m.assign = off; off += 1024 * 4;
+  m.kept = off; off += b_pad * 4;
+  m.w = off; off += b_pad * 4;
+  m.bias = off; off += b_pad * 4;
+  m.total_bytes = (off + 15) & ~15;
+  return m;
+}
 
 template <int D, int RB, int NT>
-__global__ __launch_bounds__(kF1Threads) void unit_score_kernel(Ctx c) {
+__global__ __launch_bounds__(kPThreads) void unit_plan_kernel(Ctx c, int b_pad) {
   using CF = Cfg<kBF16, D>;
-  constexpr int NCH = CF::NCH, NF = CF::NF;
+  constexpr int NCH = CF::NCH, NF = CF::NF, RS = NCH + 1;
   constexpr int ROWS = RB * 32;
-  __shared__ uint4 ldsq[ROWS * (NCH + 1)];
-  __shared__ float lds_stat[kF1Waves][ROWS];
-  __shared__ float lds_gstat[ROWS];
-  __shared__ float lds_rowimg[ROWS];
-  __shared__ float lds_cross[kF1Waves][RB];
+  extern __shared__ __align__(16) char lds_dyn[];
+  const PlanLds lay = plan_lds_layout(ROWS, b_pad, NCH);
+  uint4 *ldsq = reinterpret_cast<uint4 *>(lds_dyn + lay.q);            // [ROWS][RS] query rows
+  uint4 *lds_piv = reinterpret_cast<uint4 *>(lds_dyn + lay.piv);       // [b_pad][RS] pivot rows
+  float2 *lds_stat = reinterpret_cast<float2 *>(lds_dyn + lay.stat);   // [waves][ROWS] (max, sum exp2)
+  float *lds_c = reinterpret_cast<float *>(lds_dyn + lay.cval);        // [ROWS] max + log2(sum)
+  float *lds_rowimg = reinterpret_cast<float *>(lds_dyn + lay.rowimg); // [ROWS] 1 for an image proxy row
+  float *lds_cross = reinterpret_cast<float *>(lds_dyn + lay.cross);   // [tiles][RB] cross-modal mass per key tile
+  unsigned *lds_keys = reinterpret_cast<unsigned *>(lds_dyn + lay.keys);  // [1024] importance bits
+  int *lds_assign = reinterpret_cast<int *>(lds_dyn + lay.assign);     // [1024] slot of a pivot, -2 otherwise
+  int *lds_kept = reinterpret_cast<int *>(lds_dyn + lay.kept);         // [B]
+  float *lds_w = reinterpret_cast<float *>(lds_dyn + lay.w);           // [b_pad] 1/norm (0 for a zero row)
+  float *lds_bias = reinterpret_cast<float *>(lds_dyn + lay.bias);     // [b_pad] added to a candidate
+  __shared__ SmallSelectScratch<kPThreads> scratch;
+  __shared__ int sh_dropped;
 
   const Shape &sh = c.sh;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
-  TRACE(0);
   const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const long long unit = (long long)l * sh.Hkv + gkv;
+  TRACE(0);
 
-  // stage the query rows (zero rows pad every head to a multiple of 32)
+  // ---- every key of the unit into registers ----------------------------------------------------
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
+                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  uint4 kf[NT][NF];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int key0 = (wave + kPWaves * j) * 32;
+    if (key0 < L) {
+      const uint4 *row = K + (long long)min(key0 + n, L - 1) * sh.ks_tok + half;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) kf[j][f] = row[2 * f];
+    } else {
+#pragma unroll
+      for (int f = 0; f < NF; ++f) kf[j][f] = make_uint4(0, 0, 0, 0);
+    }
+  }
+  // the query rows (zero rows pad every head to a multiple of 32)
   {
     const uint4 *Q = reinterpret_cast<const uint4 *>(c.Q) + (long long)l * sh.qs_layer;
-    for (int idx = threadIdx.x; idx < ROWS * NCH; idx += kF1Threads) {
+    for (int idx = threadIdx.x; idx < ROWS * NCH; idx += kPThreads) {
       const int row = idx / NCH, ch = idx - row * NCH;
       const int g = row / sh.W_pad, r = row - g * sh.W_pad;
       uint4 v = make_uint4(0, 0, 0, 0);
       if (r < sh.W) v = Q[(long long)(gkv * sh.G + g) * sh.qs_head + (long long)(b * sh.W + r) * sh.qs_tok + ch];
-      ldsq[row * (NCH + 1) + ch] = v;
+      ldsq[row * RS + ch] = v;
     }
-    for (int row = threadIdx.x; row < ROWS; row += kF1Threads) {
+    for (int row = threadIdx.x; row < ROWS; row += kPThreads) {
       const int r = row % sh.W_pad;
       lds_rowimg[row] = (r < sh.W && inline_mod(c.inl, b, L - sh.W + r)) ? 1.f : 0.f;
     }
+    if (threadIdx.x == 0) sh_dropped = 0;
   }
   __syncthreads();
   TRACE(1);
 
-  // logits of this wave's key tiles: wave w owns tiles w, w+8, ... (32 keys each)
-  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
-                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
-  f32x16_t acc[NT][RB];
-  int keymod[NT];
-  // software pipeline over this wave's tiles: the loads of tile j+1 are in flight while tile j is multiplied
-  uint4 kf[2][NF];
-  auto issue = [&](int j, uint4 (&dst)[NF]) {
-    const int key0 = (wave + kF1Waves * j) * 32;
-    keymod[j] = 0;
-    if (key0 < L) {
-      const int key = min(key0 + n, L - 1);
-      keymod[j] = inline_mod(c.inl, b, key);
-      const uint4 *row = K + (long long)key * sh.ks_tok + half;
-#pragma unroll
-      for (int f = 0; f < NF; ++f) dst[f] = row[2 * f];
-    }
-  };
-  issue(0, kf[0]);
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    if (j + 1 < NT) issue(j + 1, kf[(j + 1) & 1]);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[j][rb][i] = 0.f;
-    if ((wave + kF1Waves * j) * 32 < L) {
-#pragma unroll
-      for (int f = 0; f < NF; ++f)
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          mma_chunk<kBF16>(acc[j][rb], ldsq[(rb * 32 + n) * (NCH + 1) + 2 * f + half], kf[j & 1][f]);  // [query row][key]
-    }
-  }
-
-  TRACE(2);
-  // mask, move to the log2 domain, per-row maximum over this wave's keys
   const float cl = sh.scale_log2e;
   const int wmask = sh.W_pad - 1;  // W_pad is 32 or 64 here
-  float rowv[RB][16];
+  const uint4 *qlane = ldsq + n * RS + half;  // this lane's first fragment of row block 0
+  // ---- pass 1: row statistics; accumulator rows are keys, lane n owns query row rb*32+n ----------
+  // Only the tiles that reach into the window (or past the end) pay for the causal mask.
+  {
+    float m[RB], z[RB];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = (rb * 32 + acc_row(i, half)) & wmask;
-      const int limit = r < sh.W ? L - sh.W + r : -1;
-      float m = -INFINITY;
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int key = (wave + kF1Waves * j) * 32 + n;
-        const float v = key <= limit ? acc[j][rb][i] * cl : -INFINITY;
-        acc[j][rb][i] = v;
-        m = fmaxf(m, v);
-      }
-      rowv[rb][i] = half_wave_max_hi(m);
-    }
-  if (n == 31) {
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) lds_stat[wave][rb * 32 + acc_row(i, half)] = rowv[rb][i];
-  }
-  __syncthreads();
-  if (threadIdx.x < ROWS) {
-    float m = lds_stat[0][threadIdx.x];
-#pragma unroll
-    for (int w = 1; w < kF1Waves; ++w) m = fmaxf(m, lds_stat[w][threadIdx.x]);
-    lds_gstat[threadIdx.x] = m == -INFINITY ? 0.f : m;  // padding rows: every logit is -inf
-  }
-  __syncthreads();
-
-  // exponentials and per-row sums
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float M = lds_gstat[rb * 32 + acc_row(i, half)];
-      float z = 0.f;
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const float e = fast_exp2(acc[j][rb][i] - M);
-        acc[j][rb][i] = e;
-        z += e;
-      }
-      rowv[rb][i] = half_wave_sum_hi(z);
-    }
-  if (n == 31) {
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) lds_stat[wave][rb * 32 + acc_row(i, half)] = rowv[rb][i];
-  }
-  __syncthreads();
-  if (threadIdx.x < ROWS) {
-    float z = 0.f;
-#pragma unroll
-    for (int w = 0; w < kF1Waves; ++w) z += lds_stat[w][threadIdx.x];
-    lds_gstat[threadIdx.x] = z > 0.f ? 1.0f / z : 0.f;
-  }
-  __syncthreads();
-
-  TRACE(3);
-  // probabilities reduced over the query rows: importance per key, cross-modal mass per head
-  const float inv_rows = 1.0f / (float)(sh.G * sh.W);
-  float *imp = c.importance + unit * sh.T + s.tok_off;
-  float cross_acc[RB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) cross_acc[rb] = 0.f;
-  float invz[RB][16], wimg[RB][16];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      invz[rb][i] = lds_gstat[rb * 32 + acc_row(i, half)];
-      wimg[rb][i] = lds_rowimg[rb * 32 + acc_row(i, half)];
-    }
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    float colsum = 0.f;
+    for (int rb = 0; rb < RB; ++rb) { m[rb] = -INFINITY; z[rb] = 0.f; }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float bs = 0.f, bsi = 0.f;
+      f32x16_t acc[NT];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = acc[j][rb][i] * invz[rb][i];
-        bs += p;
-        bsi = fmaf(p, wimg[rb][i], bsi);
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        const uint4 qf = qlane[rb * 32 * RS + 2 * f];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) mma_chunk<kBF16>(acc[j], kf[j][f], qf);  // [key][query row]
       }
-      colsum += bs;
-      cross_acc[rb] += keymod[j] ? bs - bsi : bsi;  // mass on keys of the other modality
-    }
-    const float tot = (colsum + __shfl_xor(colsum, 32, 64)) * inv_rows;
-    const int key = (wave + kF1Waves * j) * 32 + n;
-    if (half == 0 && key < L) imp[key] = tot;
-  }
+      const int r = (rb * 32 + n) & wmask;
+      const int limit = r < sh.W ? L - sh.W + r : -1;  // last key this query may see
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const float v = wave_sum(cross_acc[rb]);
-    if (lane == 0) lds_cross[wave][rb] = v;
+      for (int j = 0; j < NT; ++j) {
+        const int key0 = (wave + kPWaves * j) * 32;
+        if (key0 >= L) continue;
+        float tm = -INFINITY;
+        if (key0 + 31 > L - sh.W) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            acc[j][i] = key0 + acc_row(i, half) <= limit ? acc[j][i] : -INFINITY;
+            tm = fmaxf(tm, acc[j][i]);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; i += 2) tm = fmaxf(fmaxf(tm, acc[j][i]), acc[j][i + 1]);
+        }
+        if (tm > -INFINITY) {
+          const float M = fmaxf(m[rb], tm * cl);  // cl > 0: the largest logit is the largest product
+          float zt = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) zt += fast_exp2(fmaf(acc[j][i], cl, -M));
+          z[rb] = z[rb] * fast_exp2(m[rb] - M) + zt;
+          m[rb] = M;
+        }
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float m2 = __shfl_xor(m[rb], 32, 64), z2 = __shfl_xor(z[rb], 32, 64);
+      stat_combine(m[rb], z[rb], m2, z2);
+      if (half == 0) lds_stat[wave * ROWS + rb * 32 + n] = make_float2(m[rb], z[rb]);
+    }
+  }
+  TRACE(2);
+  __syncthreads();
+  if (threadIdx.x < ROWS) {
+    float2 a = lds_stat[threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < kPWaves; ++w) {
+      const float2 o = lds_stat[w * ROWS + threadIdx.x];
+      stat_combine(a.x, a.y, o.x, o.y);
+    }
+    // exp2(logit - c) is the normalised probability; padding rows get c = +inf, probability 0
+    lds_c[threadIdx.x] = ((int)threadIdx.x & wmask) < sh.W && a.y > 0.f ? a.x + __builtin_amdgcn_logf(a.y) : INFINITY;
   }
   __syncthreads();
-  if (threadIdx.x < sh.G) {
-    // head g owns the row blocks [g*W_pad/32, (g+1)*W_pad/32)
+  TRACE(3);
+
+  // ---- pass 2: probabilities reduced over the query rows; rows are query rows, lane n owns key n --
+  {
+    const float inv_rows = 1.0f / (float)(sh.G * sh.W);
+    float *imp = c.importance + unit * sh.T + s.tok_off;
+    const bool win_img = s.win_has_img != 0;
+    float colsum[NT];
+    int keymod[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      colsum[j] = 0.f;
+      keymod[j] = inline_mod(c.inl, b, min((wave + kPWaves * j) * 32 + n, L - 1));
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      f32x16_t acc[NT];
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        const uint4 qf = qlane[rb * 32 * RS + 2 * f];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) mma_chunk<kBF16>(acc[j], qf, kf[j][f]);  // [query row][key]
+      }
+      float cr[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 c4 = *reinterpret_cast<const float4 *>(lds_c + rb * 32 + 8 * g + 4 * half);
+        cr[4 * g] = c4.x; cr[4 * g + 1] = c4.y; cr[4 * g + 2] = c4.z; cr[4 * g + 3] = c4.w;
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int key0 = (wave + kPWaves * j) * 32;
+        if (key0 >= L) continue;
+        const int key = key0 + n;
+        float bs = 0.f, bsi = 0.f;
+        if (win_img || key0 + 31 > L - sh.W) {  // general form: causal mask, image rows in the window
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row = rb * 32 + acc_row(i, half);
+            float p = fast_exp2(fmaf(acc[j][i], cl, -cr[i]));  // padding rows: c = +inf, p = 0
+            p = key <= L - sh.W + (row & wmask) ? p : 0.f;
+            bs += p;
+            bsi = fmaf(p, lds_rowimg[row], bsi);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) bs += fast_exp2(fmaf(acc[j][i], cl, -cr[i]));
+        }
+        colsum[j] += bs;
+        // mass on keys of the other modality: image keys seen by text rows, text keys by image rows
+        const float cross = wave_sum(keymod[j] ? bs - bsi : bsi);
+        if (lane == 0) lds_cross[(key0 >> 5) * RB + rb] = cross;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int key = (wave + kPWaves * j) * 32 + n;
+      const float tot = (colsum[j] + __shfl_xor(colsum[j], 32, 64)) * inv_rows;
+      if (half == 0 && key < L) {
+        imp[key] = tot;
+        lds_keys[key] = __float_as_uint(tot);
+      }
+    }
+  }
+  TRACE(4);
+  __syncthreads();
+  if (wave < sh.G) {
+    // query head `wave` owns the row blocks [wave*W_pad/32, (wave+1)*W_pad/32); lane t adds tile t's
+    // share, then a fixed tree over the lanes (the same for every shape of workgroup)
     const int bph = sh.W_pad >> 5;
     float v = 0.f;
-    for (int w = 0; w < kF1Waves; ++w)
-      for (int k = 0; k < bph; ++k) v += lds_cross[w][threadIdx.x * bph + k];
-    c.cross_part[(long long)(l * sh.Hq + gkv * sh.G + threadIdx.x) * sh.tiles_score + b] = v;
+    if (lane < ((L + 31) >> 5))
+      for (int k = 0; k < bph; ++k) v += lds_cross[lane * RB + wave * bph + k];
+    v = wave_sum(v);
+    if (lane == 0) c.cross_part[(long long)(l * sh.Hq + gkv * sh.G + wave) * sh.tiles_score + b] = v;
   }
 
-  TRACE(4);
+  // ---- top-B split ---------------------------------------------------------------------------------
+  {
+    unsigned keys4[4];  // every thread's four consecutive keys (threads past the end hold none)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = threadIdx.x * 4 + j;
+      keys4[j] = i < L ? lds_keys[i] : 0u;
+    }
+    select_top_b_small<kPThreads>(keys4, L, sh.W, s.B, lds_kept, lds_assign, scratch);
+    for (int idx = s.B * NCH + (int)threadIdx.x; idx < b_pad * NCH; idx += kPThreads)  // padding pivot rows
+      lds_piv[(idx / NCH) * RS + idx % NCH] = make_uint4(0, 0, 0, 0);
+  }
+  __syncthreads();
+  TRACE(5);
+  int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  for (int i = threadIdx.x; i < s.B; i += kPThreads) kept[i] = lds_kept[i];
+
+  // ---- pivots: rows from the registers that hold them, then inverse norms and the sensitivity gate ----
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int tok = (wave + kPWaves * j) * 32 + n;
+    const int slot = tok < L ? lds_assign[tok] : -2;
+    if (slot >= 0) {
+#pragma unroll
+      for (int f = 0; f < NF; ++f) lds_piv[slot * RS + 2 * f + half] = kf[j][f];
+    }
+  }
+  __syncthreads();
+  for (int pr0 = 0; pr0 < b_pad; pr0 += kPThreads / NCH) {  // NCH lanes per row
+    const int pr = pr0 + threadIdx.x / NCH, ch = threadIdx.x % NCH;
+    float ss = pr < b_pad ? chunk_sumsq<kBF16>(lds_piv[pr * RS + ch]) : 0.f;
+#pragma unroll
+    for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if (ch == 0 && pr < b_pad) {
+      const bool ok = pr < s.B && !(__uint_as_float(lds_keys[lds_kept[pr < s.B ? pr : 0]]) > s.tau);
+      lds_w[pr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+      // added to every candidate: keeps an eligible one a normal float, sinks the others
+      lds_bias[pr] = ok ? 1e-30f : -3e38f;
+    }
+  }
+  __syncthreads();
+  TRACE(6);
+
+  // ---- match as a cross-modal layer does ---------------------------------------------------------------
+  // Each candidate is cosine * |token| (+ bias); its low four mantissa bits are replaced by 15 - i,
+  // i the row inside this lane's 16 rows of the block, so one running maximum carries the argmax.
+  int *assign = c.assign + unit * sh.T + s.tok_off;
+  const int nblk = b_pad >> 5;
+  float best[NT];
+  int best_blk[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) { best[j] = -INFINITY; best_blk[j] = 0; }
+  const uint4 *plane = lds_piv + n * RS + half;
+  for (int pb = 0; pb < nblk; ++pb) {
+    f32x16_t acc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      const uint4 pf = plane[pb * 32 * RS + 2 * f];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) mma_chunk<kBF16>(acc[j], pf, kf[j][f]);  // [pivot][token]
+    }
+    float wv[16], bv[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 w4 = *reinterpret_cast<const float4 *>(lds_w + pb * 32 + 8 * g + 4 * half);
+      const float4 b4 = *reinterpret_cast<const float4 *>(lds_bias + pb * 32 + 8 * g + 4 * half);
+      wv[4 * g] = w4.x; wv[4 * g + 1] = w4.y; wv[4 * g + 2] = w4.z; wv[4 * g + 3] = w4.w;
+      bv[4 * g] = b4.x; bv[4 * g + 1] = b4.y; bv[4 * g + 2] = b4.z; bv[4 * g + 3] = b4.w;
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      float m = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = __uint_as_float((__float_as_uint(fmaf(acc[j][i], wv[i], bv[i])) & ~15u) | (unsigned)(15 - i));
+        const float p1 = __uint_as_float((__float_as_uint(fmaf(acc[j][i + 1], wv[i + 1], bv[i + 1])) & ~15u) | (unsigned)(14 - i));
+        m = fmaxf(fmaxf(m, p0), p1);
+      }
+      if (m > best[j]) { best[j] = m; best_blk[j] = pb; }
+    }
+  }
+  int dropped = 0;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int tok = (wave + kPWaves * j) * 32 + n;
+    int best_slot = best_blk[j] * 32 + acc_row(15 - (int)(__float_as_uint(best[j]) & 15u), half);
+    const float ob = __shfl_xor(best[j], 32, 64);
+    const int os = __shfl_xor(best_slot, 32, 64);
+    float bj = best[j];
+    if (ob > bj || (ob == bj && os < best_slot)) { bj = ob; best_slot = os; }
+    if (!(bj > -1e38f)) best_slot = -1;  // no eligible pivot
+    if (half == 0 && tok < L) {
+      const int cur = lds_assign[tok];
+      assign[tok] = cur == -2 ? best_slot : cur;  // a pivot keeps its own slot
+      dropped += cur == -2 && best_slot < 0;
+    }
+  }
+  dropped = wave_sum_int(dropped);
+  if (lane == 0 && dropped) atomicAdd(&sh_dropped, dropped);
+  __syncthreads();
+  if (threadIdx.x == 0) c.n_dropped[unit * sh.batch + b] = sh_dropped;
+  TRACE(7);
 }
 
-// ============================ flow + select + match =========================================
+// ============================ flow (+ select + match of intra-modal layers) ====================
 constexpr int kF2Threads = 256;
 constexpr int kF2Waves = kF2Threads / 64;
 
@@ -279,29 +444,11 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
 
-  // the first token tile of this wave is requested before anything else
-  const int ntiles = (L + 31) >> 5;
-  uint4 kf[NF];
-  int t = wave;
-  if (t < ntiles) {
-    const uint4 *row = K + (long long)min(t * 32 + n, L - 1) * sh.ks_tok + half;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
-  }
-
-  // importances (four consecutive keys per thread) and the heads' cross-modal shares arrive together
-  unsigned keys4[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int i = threadIdx.x * 4 + j;
-    keys4[j] = i < L ? imp[i] : 0u;
-    if (i < L) lds_keys[i] = keys4[j];
-  }
+  // flow: every workgroup of the layer folds the same numbers in the same order
   for (int h = threadIdx.x; h < sh.Hq; h += kF2Threads)
     lds_head[h] = c.cross_part[(long long)(l * sh.Hq + h) * sh.tiles_score + b] / (float)sh.W;
   if (threadIdx.x == 0) sh_dropped = 0;
   __syncthreads();
-  // flow: every workgroup of the layer folds the same numbers in the same order
   if (threadIdx.x == 0) {
     float acc = 0.f;
     for (int h = 0; h < sh.Hq; ++h) acc += lds_head[h];
@@ -312,11 +459,30 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
       c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
     }
   }
+  __syncthreads();
+  const bool mode_cross = sh_rho > sh.theta;
+  if (mode_cross) return;  // unit_plan_kernel has matched this unit as a cross-modal layer does
+
+  // intra-modal layer: the split again (same result) and the match restricted to the token's modality
+  const int ntiles = (L + 31) >> 5;
+  uint4 kf[NF];
+  int t = wave;
+  if (t < ntiles) {
+    const uint4 *row = K + (long long)min(t * 32 + n, L - 1) * sh.ks_tok + half;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) kf[f] = row[2 * f];
+  }
+  unsigned keys4[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = threadIdx.x * 4 + j;
+    keys4[j] = i < L ? imp[i] : 0u;
+    if (i < L) lds_keys[i] = keys4[j];
+  }
   TRACE(9);
   // top-B split (pivot list and pivot/non-pivot marks stay in LDS; the plan gets its copy below)
   select_top_b_small<kF2Threads>(keys4, L, sh.W, s.B, lds_kept, lds_assign, scratch);
   __syncthreads();
-  const bool mode_cross = sh_rho > sh.theta;
   for (int i = threadIdx.x; i < s.B; i += kF2Threads) kept[i] = lds_kept[i];
   TRACE(10);
 
@@ -653,17 +819,30 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
 }
 
 // ---- dispatch --------------------------------------------------------------------------------
-template <int D, int RB>
-hipError_t launch_f1(const Ctx &c, int nt) {
-  const dim3 grid(c.sh.batch, c.sh.Hkv, c.sh.n_layers);
-  ProfScope ps(c.stream, KID_UNIT_SCORE);
-  switch (nt) {
-    case 1: unit_score_kernel<D, RB, 1><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-    case 2: unit_score_kernel<D, RB, 2><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-    case 3: unit_score_kernel<D, RB, 3><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-    default: unit_score_kernel<D, RB, 4><<<grid, kF1Threads, 0, c.stream>>>(c); break;
-  }
+size_t plan_lds_bytes(const Shape &sh, int b_pad) {
+  return (size_t)plan_lds_layout(sh.R_pad, b_pad, sh.d * 2 / 16).total_bytes;
+}
+
+template <int D, int RB, int NT>
+hipError_t launch_plan_k(const Ctx &c, int b_pad, size_t lds) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_plan_kernel<D, RB, NT>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  ProfScope ps(c.stream, KID_UNIT_PLAN);
+  unit_plan_kernel<D, RB, NT><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kPThreads, lds, c.stream>>>(c, b_pad);
   return hipGetLastError();
+}
+
+template <int D, int RB>
+hipError_t launch_f1(const Ctx &c) {
+  const int b_pad = (c.sh.maxB + 31) / 32 * 32;
+  const size_t lds = plan_lds_bytes(c.sh, b_pad);
+  switch (((c.sh.maxL + 31) / 32 + kPWaves - 1) / kPWaves) {  // tiles per wave
+    case 1: return launch_plan_k<D, RB, 1>(c, b_pad, lds);
+    case 2: return launch_plan_k<D, RB, 2>(c, b_pad, lds);
+    case 3: return launch_plan_k<D, RB, 3>(c, b_pad, lds);
+    default: return launch_plan_k<D, RB, 4>(c, b_pad, lds);
+  }
 }
 
 size_t match_lds_bytes(const Shape &sh, int b_pad) {
@@ -706,17 +885,16 @@ bool unit_path_fits(const Shape &sh) {
   if (!sh.bf16 || sh.maxL > 1024 || sh.R_pad > 64 || sh.maxB > 256 || sh.Hq > 4096) return false;
   if (sh.batch > kInlineSeqs || sh.n_spans > kInlineSpans) return false;  // metadata must fit the kernel arguments
   const int b_pad = (sh.maxB + 31) / 32 * 32;
-  if (match_lds_bytes(sh, b_pad) > 150 * 1024) return false;
+  if (match_lds_bytes(sh, b_pad) > 150 * 1024 || plan_lds_bytes(sh, b_pad) > 150 * 1024) return false;
   if ((size_t)merge_lds_layout(sh.maxB, sh.maxE, sh.d).total_bytes > 150 * 1024) return false;
   return true;
 }
 
-hipError_t launch_unit_plan(const Ctx &c) {
-  const int nt = ((c.sh.maxL + 31) / 32 + kF1Waves - 1) / kF1Waves;
+hipError_t launch_unit_plan(const Ctx &c) {  // score + select + cross-modal match, then flow + intra-modal layers
   const int rb = c.sh.R_pad / 32;
   hipError_t e;
-  if (c.sh.d == 128) e = rb == 1 ? launch_f1<128, 1>(c, nt) : launch_f1<128, 2>(c, nt);
-  else e = rb == 1 ? launch_f1<64, 1>(c, nt) : launch_f1<64, 2>(c, nt);
+  if (c.sh.d == 128) e = rb == 1 ? launch_f1<128, 1>(c) : launch_f1<128, 2>(c);
+  else e = rb == 1 ? launch_f1<64, 1>(c) : launch_f1<64, 2>(c);
   if (e != hipSuccess) return e;
   return c.sh.d == 128 ? launch_f2<128>(c) : launch_f2<64>(c);
 }
