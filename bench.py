@@ -30,34 +30,38 @@ def algorithmic_bytes(wl):
     s = 2 if wl.dtype == "bf16" else 4
     d, G, W = wl.head_dim, wl.group, wl.window
     units = wl.n_layers * wl.n_kv_heads
-    tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match", "merge_tasks", "select",
-                          "merge_csr", "unit_plan", "unit_match", "unit_merge")}
+    tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match_lists", "match", "merge_tasks",
+                          "select", "merge_csr", "unit_plan", "unit_merge")}
     for L, B in zip(wl.seqlens, wl.budgets):
         row = d * s
         tot["whole_pass"] += units * (3 * L * row + 2 * B * row + G * W * row + 12 * L)
         tot["score_stats"] += units * (L * row + G * W * row)              # K once, Q window
         tot["score_colsum"] += units * (L * row + G * W * row + 4 * L)     # K once, Q, importance out
         tot["select"] += units * (4 * L + 4 * L + 4 * B)                   # importance in, assign + kept out
+        tot["match_lists"] += units * (2 * B * row + 8 * B)                # pivot rows in, packed rows + tables out
         tot["match"] += units * (L * row + 4 * L + 4 * L + 4 * B)          # K once, assign in/out, kept
         tot["merge_csr"] += units * (4 * L + 4 * (L - B))                  # assign in, member list out
         tot["merge_tasks"] += units * (2 * L * row + 2 * B * row + 4 * (L - B))  # K and V rows in, compacted out
         # unit-resident kernels (short prompts)
-        tot["unit_plan"] += units * (L * row + G * W * row + 4 * L)       # K once, Q, importance out
-        tot["unit_match"] += units * (L * row + 4 * L + 4 * L + 4 * B)     # K once, importance in, assign + kept out
+        # score + select + match in one kernel: the method needs K before and after the top-B split
+        # (the split depends on every key), which is what the whole-pass figure counts; the kernel
+        # keeps the unit's keys in registers, so its measured traffic is about one K less than this
+        tot["unit_plan"] += units * (2 * L * row + G * W * row + 12 * L + 4 * B)
         tot["unit_merge"] += units * (2 * L * row + 2 * B * row + 4 * L + 4 * B)  # K, V rows, assign, kept in; compacted out
     return tot
 
 
 def measured_traffic(config: int, kernel: str):
     """HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"unit_path_config{config}_hbm_traffic.txt")
-    try:
-        for line in open(path):
-            f = [x.strip() for x in line.split("|")]
-            if not line.startswith("#") and len(f) >= 4 and f[0] == kernel:
-                return float(f[3])
-    except OSError:
-        pass
+    for tag in ("unit_path", "generic_path"):
+        path = os.path.join(ROOT, "profiles", f"{tag}_config{config}_hbm_traffic.txt")
+        try:
+            for line in open(path):
+                f = [x.strip() for x in line.split("|")]
+                if not line.startswith("#") and len(f) >= 4 and f[0] == kernel:
+                    return float(f[3])
+        except OSError:
+            pass
     return None
 
 
