@@ -30,15 +30,15 @@ def algorithmic_bytes(wl):
     s = 2 if wl.dtype == "bf16" else 4
     d, G, W = wl.head_dim, wl.group, wl.window
     units = wl.n_layers * wl.n_kv_heads
-    tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match_lists", "match", "merge_tasks",
+    tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match", "merge_tasks",
                           "select", "merge_csr", "unit_plan", "unit_merge")}
     for L, B in zip(wl.seqlens, wl.budgets):
         row = d * s
         tot["whole_pass"] += units * (3 * L * row + 2 * B * row + G * W * row + 12 * L)
         tot["score_stats"] += units * (L * row + G * W * row)              # K once, Q window
         tot["score_colsum"] += units * (L * row + G * W * row + 4 * L)     # K once, Q, importance out
-        tot["select"] += units * (4 * L + 4 * L + 4 * B)                   # importance in, assign + kept out
-        tot["match_lists"] += units * (2 * B * row + 8 * B)                # pivot rows in, packed rows + tables out
+        # importance in, assign + kept out; pivot rows in, packed rows + tables out
+        tot["select"] += units * (4 * L + 4 * L + 4 * B + 2 * B * row + 8 * B)
         tot["match"] += units * (L * row + 4 * L + 4 * L + 4 * B)          # K once, assign in/out, kept
         tot["merge_csr"] += units * (4 * L + 4 * (L - B))                  # assign in, member list out
         tot["merge_tasks"] += units * (2 * L * row + 2 * B * row + 4 * (L - B))  # K and V rows in, compacted out

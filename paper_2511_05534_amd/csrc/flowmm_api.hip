@@ -196,11 +196,12 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   rg.cross_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.tiles_score * 4);
   if (!sh.unit_path) {
     rg.pl_slot = off; off += align256((size_t)units * 2 * sh.SBP * 4);
+    rg.pl_tok = off; off += align256((size_t)units * 2 * sh.SBP * 4);
     rg.pl_w = off; off += align256((size_t)units * 2 * sh.SBP * 4);
     rg.pl_n = off; off += align256((size_t)units * batch * 2 * 4);
     rg.pack = off; off += align256((size_t)units * 2 * sh.SBP * (sh.d * es + 16));
   } else {
-    rg.pl_slot = rg.pl_w = rg.pl_n = rg.pack = off;
+    rg.pl_slot = rg.pl_tok = rg.pl_w = rg.pl_n = rg.pack = off;
   }
   rg.plan_end = off;
   off = shared0;
@@ -254,6 +255,7 @@ void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *w
   c.cross_part = reinterpret_cast<float *>(ws + lo.rg.cross_part);
   c.cls_order = reinterpret_cast<int *>(ws + lo.rg.cls_order);
   c.pl_slot = reinterpret_cast<int *>(ws + lo.rg.pl_slot);
+  c.pl_tok = reinterpret_cast<int *>(ws + lo.rg.pl_tok);
   c.pl_w = reinterpret_cast<float *>(ws + lo.rg.pl_w);
   c.pl_n = reinterpret_cast<int *>(ws + lo.rg.pl_n);
   c.pack = reinterpret_cast<uint4 *>(ws + lo.rg.pack);

@@ -27,6 +27,7 @@ struct Ctx {
   float *rowstat;      // [Lyr][Hkv][batch][R_pad]        max + log2(sum exp2) of each row, +inf for padding rows
   float *cross_part;   // [Lyr][Hq][tiles_score]          cross-modal mass of a head over a tile
   int *pl_slot;        // [Lyr][Hkv][2*SBP]               eligible pivots per (sequence, token class): their slots, ascending
+  int *pl_tok;         // [Lyr][Hkv][2*SBP]               their positions
   float *pl_w;         // [Lyr][Hkv][2*SBP]               1/norm of those pivots (0 for a zero row)
   int *pl_n;           // [Lyr][Hkv][batch][2]            list lengths, padded to multiples of 32
   uint4 *pack;         // [Lyr][Hkv][2*SBP][row chunks+1] their K rows, one chunk of padding after each

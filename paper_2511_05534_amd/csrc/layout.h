@@ -51,6 +51,7 @@ constexpr int match_tile_tokens(bool bf16) { return kMatchWaves * 32 * match_sub
 constexpr int match_tile_rows(int nch) { return 2048 / nch < 128 ? 2048 / nch : 128; }
 constexpr int kTaskChunk = 32;                               // members summed by one wave task
 constexpr int kCsrWaves = 16;                                // waves of the CSR-building workgroup
+constexpr int kFoldGroups = 4;                               // workgroups per (sequence, kv head, layer) that fold split slots
 
 struct Shape {
   int n_layers, Hq, Hkv, G, d, bf16;
@@ -80,7 +81,7 @@ struct InlineMeta {
 struct Regions {
   size_t meta, mod, cls_order;                              // both calls
   size_t part_stats, rowstat, cross_part;                   // plan: score
-  size_t pl_slot, pl_w, pl_n, pack;                         // plan: match
+  size_t pl_slot, pl_tok, pl_w, pl_n, pack;                 // plan: match
   size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials;  // merge
   size_t plan_end, merge_end;
 };

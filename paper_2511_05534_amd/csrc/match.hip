@@ -3,23 +3,18 @@
 // layer, share its modality (FlowMM, Sensitivity-Adaptive Token Matching: cosine equation and
 // thresholded argmax; the intra/cross rule of Information Flow Guided Merging).
 //
-// Two kernels.
-//   lists : per (sequence, kv head, layer) the pivots that may receive tokens are listed per
-//           token class (one class in a cross-modal layer, text / image in an intra-modal one),
-//           in ascending slot order, padded to a multiple of 32 with copies of the first entry;
-//           their K rows are packed next to each other with the row stride the match kernel's
-//           LDS tiles use (one 16-byte chunk of padding per row), and their 1/norm is tabulated.
-//           Ineligible pivots are not in any list, so the contraction below never meets them.
-//   match : a workgroup owns a tile of tokens of one class (32*KS per wave, held as MFMA B
-//           operands in registers straight from HBM) and walks over the class's pivot list in
-//           LDS tiles that arrive by direct global->LDS loads, double buffered.  The similarity
-//           matrix is never stored: each 32x32 block of dot products is scaled by the pivot's
-//           1/norm, shifted by the token's norm (so every candidate is a non-negative float whose
-//           bit pattern orders like its value) and folded into a running maximum whose low four
-//           mantissa bits carry the row inside the lane's share of the block.  The token's own
-//           norm is a positive factor common to all its candidates and is left out.
-//           Candidates therefore compare at 2^-19 relative resolution; below that the earlier
-//           list entry wins inside a lane's 16 rows of a block and the earlier block wins.
+// The select kernel leaves, per (sequence, kv head, layer) and token class (one class in a
+// cross-modal layer, text / image in an intra-modal one), the list of pivots that may receive
+// tokens, their K rows packed with the row stride used here, and their 1/norm.
+// A workgroup owns a tile of tokens of one class (32*KS per wave, held as MFMA B operands in
+// registers straight from HBM) and walks over the class's pivot list in LDS tiles that arrive by
+// direct global->LDS loads, double buffered.  The similarity matrix is never stored: each 32x32
+// block of dot products is scaled by the pivot's 1/norm, shifted by the token's norm (so every
+// candidate is a non-negative float whose bit pattern orders like its value) and folded into a
+// running maximum whose low four mantissa bits carry the row inside the lane's share of the block.
+// The token's own norm is a positive factor common to all its candidates and is left out.
+// Candidates therefore compare at 2^-19 relative resolution; below that the earlier list entry
+// wins inside a lane's 16 rows of a block and the earlier block wins.
 #include "device_common.h"
 #include "kernels.h"
 #include "profile.h"
@@ -30,7 +25,6 @@ namespace flowmm {
 namespace {
 
 constexpr int kThreads = kMatchWaves * 64;
-constexpr int kListSplit = 8;  // workgroups that share the row packing of one (sequence, kv head, layer)
 
 // Direct global -> LDS load: lane i of the wave fetches BYTES bytes from its own global address and
 // they land at lds_base + i * BYTES (lds_base wave-uniform).  Issued as inline assembly so that the
@@ -44,74 +38,6 @@ __device__ __forceinline__ void load_to_lds(const void *gptr, void *lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
   else
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
-}
-
-template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads) void match_lists_kernel(Ctx c) {
-  constexpr int NCH = Cfg<BF16, D>::NCH;
-  __shared__ int lds_wave[kThreads / 64 + 1];
-  const Shape &sh = c.sh;
-  const int *meta = c.meta;
-  const int b = blockIdx.x / kListSplit, part = blockIdx.x % kListSplit;
-  const int gkv = blockIdx.y, l = blockIdx.z;
-  const SeqInfo s = load_seq(meta, b);
-  const long long unit = (long long)l * sh.Hkv + gkv;
-  const int Bp = (s.B + 31) & ~31;
-  const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b];
-  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
-                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
-  const uint8_t *mod = c.mod + s.tok_off;
-  const float *imp = c.importance + unit * sh.T + s.tok_off;
-  const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
-  int *pl_slot = c.pl_slot + lbase;
-  float *pl_w = c.pl_w + lbase;
-  uint4 *pack = c.pack + lbase * (NCH + 1);
-  const bool cross = c.mode[l * sh.batch + b] != 0;
-
-  // ordered placement of the eligible slots of each class.  Every workgroup of the split writes
-  // the same values, so each one can read its own copy back without waiting for the others.
-  int n[2] = {0, 0};
-  for (int s0 = 0; s0 < s.B; s0 += kThreads) {
-    const int slot = s0 + threadIdx.x;
-    int f0 = 0, f1 = 0;
-    if (slot < s.B) {
-      const int tok = kept[slot];
-      const bool ok = !(imp[tok] > s.tau);
-      const int cls = cross ? 0 : mod[tok];
-      f0 = ok && cls == 0;
-      f1 = ok && cls == 1;
-    }
-    int tot;
-    const int ex = block_exclusive_scan<kThreads, int>(f0 | (f1 << 16), lds_wave, &tot);
-    if (f0) pl_slot[n[0] + (ex & 0xffff)] = slot;
-    if (f1) pl_slot[Bp + n[1] + (ex >> 16)] = slot;
-    n[0] += tot & 0xffff;
-    n[1] += tot >> 16;
-  }
-  __syncthreads();
-  const int np[2] = {(n[0] + 31) & ~31, (n[1] + 31) & ~31};
-#pragma unroll
-  for (int cls = 0; cls < 2; ++cls)
-    for (int e = n[cls] + threadIdx.x; e < np[cls]; e += kThreads) pl_slot[cls * Bp + e] = pl_slot[cls * Bp];
-  if (part == 0 && threadIdx.x < 2) c.pl_n[(unit * sh.batch + b) * 2 + threadIdx.x] = np[threadIdx.x];
-  __syncthreads();
-
-  // rows and inverse norms: NCH lanes per row, this workgroup takes every kListSplit-th pass
-  constexpr int RPP = kThreads / NCH;  // rows per pass; divides 32, so a pass is all real rows or none
-  const int rl = threadIdx.x / NCH, ch = threadIdx.x % NCH;
-#pragma unroll
-  for (int cls = 0; cls < 2; ++cls) {
-    for (int e0 = part * RPP; e0 < np[cls]; e0 += kListSplit * RPP) {
-      const int e = e0 + rl;
-      const int tok = kept[pl_slot[cls * Bp + e]];
-      const uint4 v = K[(long long)tok * sh.ks_tok + ch];
-      float ss = chunk_sumsq<BF16>(v);
-#pragma unroll
-      for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      pack[(long long)(cls * Bp + e) * (NCH + 1) + ch] = v;
-      if (ch == 0) pl_w[cls * Bp + e] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-    }
-  }
 }
 
 template <bool BF16, int D>
@@ -298,10 +224,6 @@ hipError_t launch_match_t(const Ctx &c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   constexpr int ROWS = match_tile_rows(NCH);
   const Shape &sh = c.sh;
-  {
-    ProfScope ps(c.stream, KID_MATCH_LISTS);
-    match_lists_kernel<BF16, D><<<dim3(sh.batch * kListSplit, sh.Hkv, sh.n_layers), kThreads, 0, c.stream>>>(c);
-  }
   const size_t lds = 2 * (size_t)ROWS * (NCH + 1) * 16 + 2 * ROWS * sizeof(float);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(match_kernel<BF16, D>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

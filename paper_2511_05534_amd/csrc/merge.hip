@@ -10,7 +10,8 @@
 //              cuts the slots into tasks of at most kTaskChunk members.
 //   2. tasks : one wave per task streams its rows with 16-byte loads (a wave covers 64/NCH rows
 //              per load), sums them in fp32 and either finishes the slot or leaves a partial.
-//   3. fold  : slots with several tasks add up their partials in task order.
+//   3. fold  : slots with several tasks add up their partials in task order (a few workgroups per
+//              (sequence, kv head, layer) walk over them).
 #include "device_common.h"
 #include "kernels.h"
 #include "profile.h"
@@ -243,41 +244,60 @@ __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
   }
 }
 
+// kFoldGroups workgroups per (sequence, kv head, layer) walk over its split slots, one wave per slot
 template <bool BF16, int D>
 __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
   constexpr int EPC = Cfg<BF16, D>::kElemsPerChunk;
   constexpr int NCH = Cfg<BF16, D>::NCH;
   const Shape &sh = c.sh;
   const int *meta = c.meta;
-  const int *cu = meta + meta[MW_OFF_CU_MULTI];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int q = blockIdx.x * 4 + wave;
-  if (q >= sh.multi_total) return;
+  const int b = blockIdx.x / kFoldGroups;
   const int gkv = blockIdx.y, l = blockIdx.z;
   const long long unit = (long long)l * sh.Hkv + gkv;
-  const int b = find_seq(cu, meta[MW_BATCH], q);
-  if (q - cu[b] >= c.n_multi[unit * sh.batch + b]) return;
-  const SeqInfo s = load_seq(meta, b);
-  const int4 e4 = c.multi[unit * sh.multi_total + q];  // (slot, first partial, partials, members)
-  const int pivot_tok = c.kept_idx[unit * sh.SB + s.kept_off + e4.x];
-  const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head +
-                             (long long)(s.tok_off + pivot_tok) * sh.ks_tok;
-  const float den = (float)(1 + e4.w);
-  // lanes [0, NCH) fold K chunks, lanes [NCH, 2 NCH) fold V chunks
-  for (int idx = lane; idx < 2 * NCH; idx += 64) {
-    const int tensor = idx / NCH, ch = idx % NCH;
-    const uint4 *src = reinterpret_cast<const uint4 *>(tensor ? c.V : c.K) + head_off;
-    float acc[EPC];
-    chunk_to_floats<BF16>(src[ch], acc);
-    for (int p = 0; p < e4.z; ++p) {
-      const float *pp = c.partials + ((unit * sh.part_total + e4.y + p) * 2 + tensor) * D + ch * EPC;
+  const int n_multi = c.n_multi[unit * sh.batch + b];
+  const int q0 = (meta + meta[MW_OFF_CU_MULTI])[b];
+  for (int qm = (blockIdx.x % kFoldGroups) * 4 + wave; qm < n_multi; qm += kFoldGroups * 4) {
+    const int q = q0 + qm;
+    const SeqInfo s = load_seq(meta, b);
+    const int4 e4 = c.multi[unit * sh.multi_total + q];  // (slot, first partial, partials, members)
+    const int pivot_tok = c.kept_idx[unit * sh.SB + s.kept_off + e4.x];
+    const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head +
+                               (long long)(s.tok_off + pivot_tok) * sh.ks_tok;
+    const float den = (float)(1 + e4.w);
+    // lanes [0, NCH) fold K chunks, lanes [NCH, 2 NCH) fold V chunks
+    for (int idx = lane; idx < 2 * NCH; idx += 64) {
+      const int tensor = idx / NCH, ch = idx % NCH;
+      const uint4 *src = reinterpret_cast<const uint4 *>(tensor ? c.V : c.K) + head_off;
+      float acc[EPC];
+      chunk_to_floats<BF16>(src[ch], acc);
+      constexpr int U = 8;  // partials in flight; they are added in task order all the same
+      for (int p0 = 0; p0 < e4.z; p0 += U) {
+        float part[U][EPC];
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[e] += pp[e];
+        for (int u = 0; u < U; ++u) {
+          if (p0 + u < e4.z) {
+            const float *pp = c.partials + ((unit * sh.part_total + e4.y + p0 + u) * 2 + tensor) * D + ch * EPC;
+#pragma unroll
+            for (int e = 0; e < EPC; e += 4) {
+              const float4 f4 = *reinterpret_cast<const float4 *>(pp + e);
+              part[u][e] = f4.x; part[u][e + 1] = f4.y; part[u][e + 2] = f4.z; part[u][e + 3] = f4.w;
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (p0 + u < e4.z) {
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) acc[e] += part[u][e];
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] = acc[e] / den;
+      const long long orow = (unit * sh.SB + s.kept_off + e4.x) * NCH + ch;
+      reinterpret_cast<uint4 *>(tensor ? c.V_out : c.K_out)[orow] = floats_to_chunk<BF16>(acc);
     }
-#pragma unroll
-    for (int e = 0; e < EPC; ++e) acc[e] = acc[e] / den;
-    const long long orow = (unit * sh.SB + s.kept_off + e4.x) * NCH + ch;
-    reinterpret_cast<uint4 *>(tensor ? c.V_out : c.K_out)[orow] = floats_to_chunk<BF16>(acc);
   }
 }
 
@@ -297,7 +317,7 @@ hipError_t launch_merge_t(const Ctx &c, int nw_shift, size_t lds) {
   }
   {
     ProfScope ps(c.stream, KID_MERGE_FOLD);
-    merge_fold_kernel<BF16, D><<<dim3((sh.multi_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+    merge_fold_kernel<BF16, D><<<dim3(sh.batch * kFoldGroups, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
   }
   return hipGetLastError();
 }

@@ -1,10 +1,16 @@
-// Steps "flow" and "select".
+// Steps "flow" and "select", and the lists the match step works from.
 //   flow  : rho = mean over query heads of the share of proxy attention that lands on tokens
 //           of the other modality; the layer merges across modalities iff rho > theta
 //           (FlowMM, Information Flow Guided Merging: rho equation and threshold rule).
 //   select: the B most important tokens of each KV head form the pivot set, the rest are
 //           merged into it (same section, top-B rule).  The proxy tokens themselves are always
 //           pivots.  Ties go to the lower position, pivots are listed in ascending position.
+//   lists : the pivots that may receive tokens (importance <= tau: Sensitivity-Adaptive Token
+//           Matching), per token class (one class in a cross-modal layer, text / image in an
+//           intra-modal one), in ascending slot order, padded to a multiple of 32 with copies of
+//           the first entry; their K rows packed next to each other with the row stride of the
+//           match kernel's LDS tiles (one 16-byte chunk of padding per row), and their 1/norm.
+//           Ineligible pivots are in no list, so the match contraction never meets them.
 // One workgroup per (sequence, kv head, layer).  The B-th largest importance is found by a
 // 4-pass radix select on the float bit patterns (importances are non-negative, so the bits
 // order like the values); a block-wide ordered scan then compacts the pivots.
@@ -19,17 +25,23 @@ namespace {
 
 constexpr int kThreads = 1024;
 
+template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
+  constexpr int NCH = Cfg<BF16, D>::NCH;
   __shared__ SelectScratch<kThreads> scratch;
   __shared__ float lds_head[kThreads];
+  __shared__ float sh_rho;
   const Shape &sh = c.sh;
+  const int *meta = c.meta;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
-  const SeqInfo s = load_seq(c.meta, b);
+  const SeqInfo s = load_seq(meta, b);
+  const long long unit = (long long)l * sh.Hkv + gkv;
 
-  // ---- flow (one workgroup per sequence and layer does it) ------------------------------
-  if (gkv == 0) {
-    const int *cu = c.meta + c.meta[MW_OFF_CU_SCORE];
+  // ---- flow: every workgroup of the layer folds the same numbers in the same order -------------
+  {
+    const int *cu = meta + meta[MW_OFF_CU_SCORE];
     const int x0 = cu[b], x1 = cu[b + 1];
+    float rho = 0.f;
     for (int h0 = 0; h0 < sh.Hq; h0 += kThreads) {
       const int h = h0 + threadIdx.x;
       if (h < sh.Hq) {
@@ -40,34 +52,117 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
       }
       __syncthreads();
       if (threadIdx.x == 0) {
-        float acc = h0 == 0 ? 0.f : c.rho[l * sh.batch + b];
         const int nh = min(kThreads, sh.Hq - h0);
-        for (int i = 0; i < nh; ++i) acc += lds_head[i];
-        c.rho[l * sh.batch + b] = acc;
+        for (int i = 0; i < nh; ++i) rho += lds_head[i];
       }
       __syncthreads();
     }
     if (threadIdx.x == 0) {
-      const float rho = c.rho[l * sh.batch + b] / (float)sh.Hq;
-      c.rho[l * sh.batch + b] = rho;
-      c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
+      rho /= (float)sh.Hq;
+      sh_rho = rho;
+      if (gkv == 0) {
+        c.rho[l * sh.batch + b] = rho;
+        c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
+      }
+      c.n_dropped[unit * sh.batch + b] = 0;
     }
   }
-  if (threadIdx.x == 0) c.n_dropped[(l * sh.Hkv + gkv) * sh.batch + b] = 0;
 
   // ---- top-B split -----------------------------------------------------------------------------
-  const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) +
-                        (long long)(l * sh.Hkv + gkv) * sh.T + s.tok_off;
-  int *kept = c.kept_idx + (long long)(l * sh.Hkv + gkv) * sh.SB + s.kept_off;
-  int *assign = c.assign + (long long)(l * sh.Hkv + gkv) * sh.T + s.tok_off;
+  const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
+  int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  int *assign = c.assign + unit * sh.T + s.tok_off;
   select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
+  __syncthreads();  // kept[] is read back below; sh_rho is set
+  const bool cross = sh_rho > sh.theta;
+
+  // ---- lists of eligible pivots per token class --------------------------------------------------
+  const int Bp = (s.B + 31) & ~31;
+  const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b];
+  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
+                   (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
+  const uint8_t *mod = c.mod + s.tok_off;
+  const float *impf = c.importance + unit * sh.T + s.tok_off;
+  int *pl_slot = c.pl_slot + lbase;
+  int *pl_tok = c.pl_tok + lbase;
+  float *pl_w = c.pl_w + lbase;
+  uint4 *pack = c.pack + lbase * (NCH + 1);
+  int n[2] = {0, 0};
+  for (int s0 = 0; s0 < s.B; s0 += kThreads) {  // ordered placement of the eligible slots of each class
+    const int slot = s0 + threadIdx.x;
+    int f0 = 0, f1 = 0, tok = 0;
+    if (slot < s.B) {
+      tok = kept[slot];
+      const bool ok = !(impf[tok] > s.tau);
+      const int cls = cross ? 0 : mod[tok];
+      f0 = ok && cls == 0;
+      f1 = ok && cls == 1;
+    }
+    int tot;
+    const int ex = block_exclusive_scan<kThreads, int>(f0 | (f1 << 16), scratch.wave_sums, &tot);
+    if (f0 | f1) {
+      const int pos = f0 ? n[0] + (ex & 0xffff) : Bp + n[1] + (ex >> 16);
+      pl_slot[pos] = slot;
+      pl_tok[pos] = tok;
+    }
+    n[0] += tot & 0xffff;
+    n[1] += tot >> 16;
+  }
+  __syncthreads();
+  const int np[2] = {(n[0] + 31) & ~31, (n[1] + 31) & ~31};
+#pragma unroll
+  for (int cls = 0; cls < 2; ++cls)
+    for (int e = n[cls] + threadIdx.x; e < np[cls]; e += kThreads) {
+      pl_slot[cls * Bp + e] = pl_slot[cls * Bp];
+      pl_tok[cls * Bp + e] = pl_tok[cls * Bp];
+    }
+  if (threadIdx.x < 2) c.pl_n[(unit * sh.batch + b) * 2 + threadIdx.x] = np[threadIdx.x];
+  __syncthreads();
+  // rows and inverse norms: NCH lanes per row
+  constexpr int RPP = kThreads / NCH;  // rows per pass; a multiple of 32, so a pass ends inside a padded list
+  const int rl = threadIdx.x / NCH, ch = threadIdx.x % NCH;
+  constexpr int U = 4;  // rows in flight per lane group: the dependent loads of a row overlap with the others'
+#pragma unroll
+  for (int cls = 0; cls < 2; ++cls) {
+    for (int e0 = 0; e0 < np[cls]; e0 += U * RPP) {
+      int e[U], tok[U];
+      uint4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        e[u] = e0 + u * RPP + rl;  // e < np is uniform over the NCH lanes of a row
+        tok[u] = e[u] < np[cls] ? pl_tok[cls * Bp + e[u]] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        v[u] = make_uint4(0, 0, 0, 0);
+        if (e[u] < np[cls]) v[u] = K[(long long)tok[u] * sh.ks_tok + ch];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float ss = chunk_sumsq<BF16>(v[u]);
+#pragma unroll
+        for (int o = NCH / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if (e[u] < np[cls]) {
+          pack[(long long)(cls * Bp + e[u]) * (NCH + 1) + ch] = v[u];
+          if (ch == 0) pl_w[cls * Bp + e[u]] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+        }
+      }
+    }
+  }
 }
 
 }  // namespace
 
 hipError_t launch_select(const Ctx &c) {
   ProfScope ps(c.stream, KID_SELECT);
-  select_kernel<<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kThreads, 0, c.stream>>>(c);
+  const dim3 grid(c.sh.batch, c.sh.Hkv, c.sh.n_layers);
+  if (c.sh.bf16) {
+    if (c.sh.d == 128) select_kernel<true, 128><<<grid, kThreads, 0, c.stream>>>(c);
+    else select_kernel<true, 64><<<grid, kThreads, 0, c.stream>>>(c);
+  } else {
+    if (c.sh.d == 128) select_kernel<false, 128><<<grid, kThreads, 0, c.stream>>>(c);
+    else select_kernel<false, 64><<<grid, kThreads, 0, c.stream>>>(c);
+  }
   return hipGetLastError();
 }
 
