@@ -35,6 +35,9 @@ SMALL_CASES = {
     "cross_forced": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), theta=-1.0),
     "gate_off": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), tau_factor=float("inf")),
     "gate_drops_everything": dict(Hq=4, Hkv=2, spans=((40, 300, 60),), tau_factor=-1.0),
+    "unit_four_tiles_per_wave": dict(Hq=2, Hkv=2, W=32, spans=((60, 880, 60),), pct=(20,)),
+    "unit_d64": dict(Hq=2, Hkv=2, d=64, W=24, spans=((50, 500, 77),)),
+    "unit_two_row_blocks_gqa": dict(Hq=4, Hkv=2, W=32, spans=((20, 600, 40),), pct=(12,)),
     "shortest": dict(Hq=1, Hkv=1, W=1, spans=((1,),), budgets=(1,), n_layers=1),
     "tiny_3_tokens": dict(Hq=2, Hkv=1, W=2, spans=((1, 2),), budgets=(2,), n_layers=1),
 }
