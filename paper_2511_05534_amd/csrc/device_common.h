@@ -151,12 +151,16 @@ __device__ __forceinline__ SeqInfo inline_seq(const InlineMeta &m, int b) {
   return s;
 }
 
-// modality (0 text, 1 image) of position i of sequence b: the first span that ends after i
+// modality (0 text, 1 image) of position i of sequence b: the first span that ends after i.
+// The loop runs over the spans of the sequence with wave-uniform bounds, so the span table is read
+// with scalar loads (a per-lane walk would turn it into vector loads from the argument block, which
+// then queue behind every outstanding key load).
 __device__ __forceinline__ int inline_mod(const InlineMeta &m, int b, int i) {
-  int j = m.span_off[b];
-  const int last = m.span_off[b + 1] - 1;
-  while (j < last && i >= m.span_end[j]) ++j;
-  return (m.span_is_image >> j) & 1u;
+  const int first = m.span_off[b], last = m.span_off[b + 1] - 1;
+  int mod = (m.span_is_image >> last) & 1u;
+  for (int j = last - 1; j >= first; --j)
+    if (i < m.span_end[j]) mod = (m.span_is_image >> j) & 1u;
+  return mod;
 }
 
 }  // namespace flowmm
