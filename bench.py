@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the FlowMM prefill-time KV-cache merge on one MI355X.
 
-A step is one pass of the whole hot path (flowmm_plan + flowmm_merge: score, flow, select,
+A step is one pass of the whole hot path (flowmm_plan_merge = flowmm_plan + flowmm_merge: score, flow, select,
 match, merge) over every layer and head of one synthetic prefill cache that already sits in
 HBM.  Prints ONE JSON line: tokens merged per second, the roofline of the dominant kernel
 (timed live with HIP events on the launch stream) and the CPU oracle timed on the host cores.
@@ -31,7 +31,7 @@ def algorithmic_bytes(wl):
     d, G, W = wl.head_dim, wl.group, wl.window
     units = wl.n_layers * wl.n_kv_heads
     tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match", "merge_tasks",
-                          "select", "merge_csr", "unit_plan", "unit_merge")}
+                          "select", "merge_csr", "unit_plan", "unit_merge", "unit_stream_plan", "unit_stream_merge")}
     for L, B in zip(wl.seqlens, wl.budgets):
         row = d * s
         tot["whole_pass"] += units * (3 * L * row + 2 * B * row + G * W * row + 12 * L)
@@ -48,6 +48,10 @@ def algorithmic_bytes(wl):
         # keeps the unit's keys in registers, so its measured traffic is about one K less than this
         tot["unit_plan"] += units * (2 * L * row + G * W * row + 12 * L + 4 * B)
         tot["unit_merge"] += units * (2 * L * row + 2 * B * row + 4 * L + 4 * B)  # K, V rows, assign, kept in; compacted out
+        tot["unit_stream_plan"] = tot["unit_plan"]
+        # the one kernel that takes a unit from its keys to its merged rows: the whole-pass figure less the
+        # round trip of the importances (written for the caller, not read back)
+        tot["unit_stream_merge"] += units * (3 * L * row + 2 * B * row + G * W * row + 8 * L + 4 * B)
     return tot
 
 
@@ -95,6 +99,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the metric's configuration)")
     ap.add_argument("--layers", type=int, default=0,
                     help="depth override for kernel tuning runs (0 = the configuration's own depth, which the metric needs)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="run flowmm_plan then flowmm_merge instead of the one-call flowmm_plan_merge")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -122,8 +128,11 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
 
     def step():
-        bufs.plan(K, Q, stream)
-        bufs.merge(K, V, stream)
+        if args.two_calls:
+            bufs.plan(K, Q, stream)
+            bufs.merge(K, V, stream)
+        else:
+            bufs.plan_merge(K, V, Q, stream)
 
     if args.pmc_calibrate:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -169,6 +178,7 @@ def main():
         "config": {"workload": f"configs[{args.config}] {wl.name}", "layers": wl.n_layers, "q_heads": wl.n_q_heads,
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "seqlens": wl.seqlens, "budgets": wl.budgets,
                    "window": wl.window, "theta": wl.theta, "tokens_per_step": wl.total_tokens,
+                   "entry_point": "flowmm_plan + flowmm_merge" if args.two_calls else "flowmm_plan_merge",
                    "token_layer_kvheads_per_s": tokens_per_s * wl.n_layers * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

@@ -111,6 +111,15 @@ flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *pl
                            const void *V, void *K_out, void *V_out, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* flowmm_plan followed by flowmm_merge in one call, with the same arguments, results and rules:
+ * the plan buffers are filled as flowmm_plan fills them and K_out, V_out as flowmm_merge does
+ * from that plan (the whole method of the paper's Method section, score to merged cache).  The
+ * caller who does not want to look at the plan in between saves the argument checks, one
+ * metadata upload and, for short prompts, one kernel launch. */
+flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K, const void *V, const void *Q_window,
+                                const flowmm_plan_buffers *plan, void *K_out, void *V_out, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
 /* Message of the last failing call on this thread (static storage, never NULL). */
 const char *flowmm_last_error(void);
 

@@ -19,7 +19,7 @@ FLOWMM_F32, FLOWMM_BF16 = 0, 1
 FLOWMM_FLAG_GENERIC_PATH = 1
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
-EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_last_error",
+EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_last_error",
            "flowmm_profile_kernel_count", "flowmm_profile_kernel_name", "flowmm_profile_select",
            "flowmm_profile_collect")
 
@@ -72,7 +72,10 @@ def load(build_if_missing: bool = True):
                                     C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_size_t, C.c_void_p]
         lib.flowmm_merge.argtypes = [C.POINTER(flowmm_params), C.POINTER(flowmm_plan_buffers), C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-        for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge, lib.flowmm_profile_collect,
+        lib.flowmm_plan_merge.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
+        for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge, lib.flowmm_plan_merge, lib.flowmm_profile_collect,
                   lib.flowmm_profile_kernel_count):
             f.restype = C.c_int
         lib.flowmm_profile_kernel_name.restype = C.c_char_p
@@ -158,6 +161,14 @@ def flowmm_merge(params: Params, plan_ptrs: Sequence[int], K: int, V: int, K_out
                                C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
+def flowmm_plan_merge(params: Params, K: int, V: int, Q_window: int, plan_ptrs: Sequence[int], K_out: int,
+                      V_out: int, workspace: int, workspace_bytes: int, stream: int = 0):
+    pb = _plan_struct(plan_ptrs)
+    _check(load().flowmm_plan_merge(C.byref(params.c), C.c_void_p(K), C.c_void_p(V), C.c_void_p(Q_window),
+                                    C.byref(pb), C.c_void_p(K_out), C.c_void_p(V_out), C.c_void_p(workspace),
+                                    C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+
 def flowmm_profile_select(names: str = ""):
     load().flowmm_profile_select(names.encode())
 
@@ -217,6 +228,11 @@ class DeviceBuffers:
     def plan(self, K, Q, stream: int = 0):
         flowmm_plan(self.params, K.data_ptr(), Q.data_ptr(), self.plan_ptrs, self.workspace.data_ptr(),
                     self.workspace_bytes, stream)
+
+    def plan_merge(self, K, V, Q, stream: int = 0):
+        flowmm_plan_merge(self.params, K.data_ptr(), V.data_ptr(), Q.data_ptr(), self.plan_ptrs,
+                          self.K_out.data_ptr(), self.V_out.data_ptr(), self.workspace.data_ptr(),
+                          self.workspace_bytes, stream)
 
     def merge(self, K, V, stream: int = 0):
         flowmm_merge(self.params, self.plan_ptrs, K.data_ptr(), V.data_ptr(), self.K_out.data_ptr(),

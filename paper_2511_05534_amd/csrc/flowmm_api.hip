@@ -245,6 +245,8 @@ void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *w
   c.sh = lo.sh;
   c.inl = lo.inl;
   c.stream = reinterpret_cast<hipStream_t>(stream);
+  c.layer0 = 0;
+  c.layers = lo.sh.n_layers;
   c.importance = plan->importance; c.rho = plan->rho; c.mode = plan->mode;
   c.kept_idx = plan->kept_idx; c.assign = plan->assign; c.n_dropped = plan->n_dropped;
   char *ws = reinterpret_cast<char *>(workspace);
@@ -316,17 +318,14 @@ FLOWMM_API flowmm_status flowmm_plan(const flowmm_params *p, const void *K, cons
   return FLOWMM_OK;
 }
 
-FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *plan, const void *K,
-                           const void *V, void *K_out, void *V_out, void *workspace,
-                           size_t workspace_bytes, void *stream) {
-  Layout lo;
-  flowmm_status st = build_layout(p, lo);
-  if (st != FLOWMM_OK) return st;
-  if (!K || !V || !K_out || !V_out || !workspace)
-    return fail(FLOWMM_EINVAL, "K, V, K_out, V_out and workspace must not be NULL");
-  if (misaligned(K) || misaligned(V) || misaligned(K_out) || misaligned(V_out) || misaligned(workspace))
-    return fail(FLOWMM_EINVAL, "K, V, K_out, V_out and workspace must be 16-byte aligned");
-  if ((st = check_plan_buffers(plan)) != FLOWMM_OK) return st;
+}  // extern "C"
+
+namespace {
+
+flowmm_status check_merge_args(const Layout &lo, const void *K, const void *V, void *K_out, void *V_out) {
+  if (!K || !V || !K_out || !V_out) return fail(FLOWMM_EINVAL, "K, V, K_out and V_out must not be NULL");
+  if (misaligned(K) || misaligned(V) || misaligned(K_out) || misaligned(V_out))
+    return fail(FLOWMM_EINVAL, "K, V, K_out and V_out must be 16-byte aligned");
   const size_t out_bytes = (size_t)lo.sh.n_layers * lo.sh.Hkv * lo.sh.SB * lo.sh.d * (lo.sh.bf16 ? 2 : 4);
   const void *ins[2] = {K, V};
   void *outs[2] = {K_out, V_out};
@@ -335,6 +334,22 @@ FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_
       if (overlaps(outs[i], out_bytes, ins[j], lo.kv_extent_bytes))
         return fail(FLOWMM_EINVAL, "outputs must not overlap K or V (in-place compaction is not supported)");
   if (overlaps(K_out, out_bytes, V_out, out_bytes)) return fail(FLOWMM_EINVAL, "K_out and V_out overlap");
+  return FLOWMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *plan, const void *K,
+                           const void *V, void *K_out, void *V_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (!workspace || misaligned(workspace)) return fail(FLOWMM_EINVAL, "workspace must be a 16-byte aligned device pointer");
+  if ((st = check_merge_args(lo, K, V, K_out, V_out)) != FLOWMM_OK) return st;
+  if ((st = check_plan_buffers(plan)) != FLOWMM_OK) return st;
   if (workspace_bytes < lo.workspace_bytes)
     return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
   Ctx c;
@@ -346,6 +361,36 @@ FLOWMM_API flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_
     return FLOWMM_OK;
   }
   if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), false)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K, const void *V, const void *Q_window,
+                                const flowmm_plan_buffers *plan, void *K_out, void *V_out, void *workspace,
+                                size_t workspace_bytes, void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (!Q_window || !workspace) return fail(FLOWMM_EINVAL, "Q_window and workspace must not be NULL");
+  if (misaligned(Q_window) || misaligned(workspace)) return fail(FLOWMM_EINVAL, "Q_window and workspace must be 16-byte aligned");
+  if ((st = check_merge_args(lo, K, V, K_out, V_out)) != FLOWMM_OK) return st;
+  if ((st = check_plan_buffers(plan)) != FLOWMM_OK) return st;
+  if (workspace_bytes < lo.workspace_bytes)
+    return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
+  Ctx c;
+  fill_ctx(c, lo, plan, workspace, stream);
+  c.K = K; c.V = V; c.Q = Q_window; c.K_out = K_out; c.V_out = V_out;
+  hipError_t e;
+  if (c.sh.unit_path) {
+    if ((e = launch_unit_plan(c, false)) != hipSuccess) return hip_fail(e, "unit-resident plan kernel");
+    if ((e = launch_unit_merge(c, true)) != hipSuccess) return hip_fail(e, "unit-resident flow and merge kernel");
+    return FLOWMM_OK;
+  }
+  // the metadata block sits in front of the scratch that the plan and the merge kernels share, so one upload serves both
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_score(c)) != hipSuccess) return hip_fail(e, "score kernels");
+  if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
+  if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
   if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
   return FLOWMM_OK;
 }

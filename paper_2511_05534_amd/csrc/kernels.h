@@ -12,6 +12,7 @@ struct Ctx {
   Shape sh;
   InlineMeta inl;  // valid when sh.unit_path
   hipStream_t stream;
+  int layer0, layers;  // the unit-resident kernels work on layers [layer0, layer0 + layers) per launch
   // inputs
   const void *K, *V, *Q;
   // plan buffers
@@ -51,8 +52,12 @@ hipError_t launch_merge(const Ctx &c);    // CSR build, task sums, combine
 
 // unit-resident path (short prompts): one workgroup per (sequence, kv head, layer)
 bool unit_path_fits(const Shape &sh);
-hipError_t launch_unit_plan(const Ctx &c);   // score, flow+select+match
-hipError_t launch_unit_merge(const Ctx &c);
+// score, select and the cross-modal match of every unit; with_flow adds the launch that settles the
+// layer strategies and matches the units of intra-modal layers again (the plan is then complete)
+hipError_t launch_unit_plan(const Ctx &c, bool with_flow = true);
+hipError_t launch_unit_flow_match(const Ctx &c);
+// merge; with_flow: the same workgroups first do what launch_unit_flow_match does for their unit
+hipError_t launch_unit_merge(const Ctx &c, bool with_flow = false);
 
 // static LDS needs, used by the host to reject shapes that cannot be staged
 size_t score_lds_bytes(const Shape &sh);

@@ -15,25 +15,14 @@
 #include "kernels.h"
 #include "profile.h"
 #include "select_core.h"
+#include "trace.h"
+#include "unit_merge_core.h"
 
 namespace flowmm {
 
 namespace {
 
 constexpr bool kBF16 = true;
-
-// Build with -DFLOWMM_TRACE to make thread 0 of every workgroup stamp the 100 MHz wall clock at
-// the phase boundaries below into a buffer set through flowmm_trace_set (kernel tuning only).
-#ifdef FLOWMM_TRACE
-static __device__ unsigned long long *g_trace;
-#define TRACE(k)                                                                                          \
-  do {                                                                                                    \
-    if (threadIdx.x == 0)                                                                                 \
-      g_trace[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (k)] = wall_clock64(); \
-  } while (0)
-#else
-#define TRACE(k)
-#endif
 
 // ============================ score + select + match (cross-modal) ===========================
 // One workgroup of eight waves per unit.  Wave w keeps the key tiles w, w+8, ... (32 keys each) in
@@ -92,7 +81,7 @@ __global__ __launch_bounds__(kPThreads) void unit_plan_kernel(Ctx c, int b_pad) 
   __shared__ int sh_dropped;
 
   const Shape &sh = c.sh;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z + c.layer0;
   const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
@@ -414,11 +403,11 @@ __host__ __device__ inline MatchLds match_lds_layout(int b_pad, int nch, int Hq,
   return m;
 }
 
+// All 256 threads of the workgroup of unit (b, gkv, l) call; lds_dyn: match_lds_layout bytes.
 template <int D>
-__global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad) {
+__device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, char *lds_dyn, int b, int gkv, int l) {
   using CF = Cfg<kBF16, D>;
   constexpr int NCH = CF::NCH, NF = CF::NF;
-  extern __shared__ __align__(16) char lds_dyn[];
   const MatchLds lay = match_lds_layout(b_pad, NCH, c.sh.Hq, c.sh.maxL);
   uint4 *lds_piv = reinterpret_cast<uint4 *>(lds_dyn + lay.piv);     // [b_pad][NCH+1] pivot rows
   float *lds_w = reinterpret_cast<float *>(lds_dyn + lay.w);         // [b_pad] 1/norm (0 for a zero row)
@@ -432,7 +421,6 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   __shared__ int sh_dropped;
 
   const Shape &sh = c.sh;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
   TRACE(8);
   const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
@@ -557,265 +545,32 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
   if (threadIdx.x == 0) c.n_dropped[unit * sh.batch + b] = sh_dropped;
 }
 
-// ============================ merge =========================================================
-constexpr int kF3Threads = 256;
-constexpr int kF3Waves = kF3Threads / 64;
-constexpr int kF3Chunks = 4;   // 64-token chunks a wave walks: ceil(1024 / 4 waves / 64)
-constexpr int kUnitChunk = 64;  // members per task of a slot that is cut up (keeps the partial sums in LDS few)
-
-struct MergeLds {  // element offsets (ints) into the dynamic LDS block
-  int tbl, kept, copies, members, tasks, multi, partials, total_bytes;
-};
-
-__host__ __device__ inline MergeLds merge_lds_layout(int maxB, int maxE, int d) {
-  MergeLds m;
-  int off = 0;
-  m.tbl = off; off += maxB * kF3Waves;
-  m.kept = off; off += maxB;
-  m.copies = off; off += maxB;
-  m.members = off; off += maxE + 1;
-  off = (off + 3) & ~3;
-  m.tasks = off; off += 4 * (maxB + maxE / kUnitChunk + 1);
-  m.multi = off; off += 4 * (maxE / (kUnitChunk + 1) + 1);
-  m.partials = off; off += (2 * (maxE / kUnitChunk) + 2) * 2 * d;
-  m.total_bytes = off * 4;
-  return m;
-}
-
-__device__ __forceinline__ unsigned long long same_slot_lanes(bool member, int slot, int nbits) {
-  unsigned long long m = __ballot(member);
-  for (int bit = 0; bit < nbits; ++bit) {
-    const bool one = (slot >> bit) & 1;
-    const unsigned long long bb = __ballot(member && one);
-    m &= one ? bb : ~bb;
-  }
-  return m;
-}
-
-// One workgroup per unit.  A stable counting sort groups the evicted tokens by slot in LDS; then
-// every group of LPR lanes (one 16-byte chunk per lane, so a group covers one row per load)
-// works on its own: pivots nobody merges into are copied, U rows in flight per group; the other
-// slots become tasks (a slot, or a chunk of at most kUnitChunk members of a larger slot) that a
-// group adds up row after row, U row loads in flight, large chunks first; slots cut into several
-// tasks are folded from their partial sums at the end.
 template <int D>
-__global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB, int maxE) {
-  using CF = Cfg<kBF16, D>;
-  constexpr int LPR = CF::NCH, RPL = 64 / LPR, EPC = CF::kElemsPerChunk, U = 8;
+__global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad) {
+  extern __shared__ __align__(16) char lds_dyn[];
+  unit_flow_match_body<D>(c, b_pad, lds_dyn, blockIdx.x, blockIdx.y, blockIdx.z + c.layer0);
+}
+
+// ============================ merge =========================================================
+// Merge of one unit per workgroup (unit_merge_core.h).  U rows in flight per lane group.
+// FLOW: the workgroup first settles its layer's strategy and, in an intra-modal layer, matches its
+// unit again (what unit_match_kernel does), so that plan and merge take two launches, not three.
+template <int D, int U, bool FLOW>
+__global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB, int maxE, int b_pad) {
   extern __shared__ __align__(16) int lds_i[];
   __shared__ long long lds_wave[kF3Waves + 1];
-  __shared__ int sh_next;  // next task nobody has taken yet
-  const MergeLds lay = merge_lds_layout(maxB, maxE, D);
-  int *tbl = lds_i + lay.tbl;          // [B][waves] members per wave range, later write cursors
-  int *lds_kept = lds_i + lay.kept;    // [B] pivot positions
-  int *copies = lds_i + lay.copies;    // slots without members
-  int *members = lds_i + lay.members;  // evicted tokens grouped by slot, ascending
-  int4 *tasks = reinterpret_cast<int4 *>(lds_i + lay.tasks);  // (slot, first member, members, partial or -1)
-  int4 *multi = reinterpret_cast<int4 *>(lds_i + lay.multi);  // (slot, first partial, partials, members)
-  float *partials = reinterpret_cast<float *>(lds_i + lay.partials);
-
+  __shared__ int sh_next;
   const Shape &sh = c.sh;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z + c.layer0;
+  if constexpr (FLOW) {
+    static_assert(kF2Threads == kF3Threads, "one workgroup runs both bodies");
+    unit_flow_match_body<D>(c, b_pad, reinterpret_cast<char *>(lds_i), b, gkv, l);
+    __syncthreads();  // the assignment written above is read below; the LDS block changes hands
+  }
   const SeqInfo s = inline_seq(c.inl, b);
   const long long unit = (long long)l * sh.Hkv + gkv;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int *assign = c.assign + unit * sh.T + s.tok_off;
-  const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
-  constexpr int NW = kF3Waves;
-
-  TRACE(0);
-  int nbits = 0;
-  while ((1 << nbits) < s.B) ++nbits;
-  const int range = ((s.L + NW - 1) / NW + 63) & ~63;  // <= 64 * kF3Chunks since L <= 1024
-  const int r0 = wave * range, r1 = min(s.L, r0 + range);
-
-  // this wave's assignments and the pivot list arrive in one round trip
-  int slot_of[kF3Chunks];
-#pragma unroll
-  for (int k = 0; k < kF3Chunks; ++k) {
-    const int i = r0 + k * 64 + lane;
-    slot_of[k] = i < r1 ? assign[i] : -1;
-  }
-  for (int i = threadIdx.x; i < s.B; i += kF3Threads) lds_kept[i] = kept[i];
-  for (int i = threadIdx.x; i < s.B * NW; i += kF3Threads) tbl[i] = 0;
-  if (threadIdx.x == 0) sh_next = kF3Waves * (64 / CF::NCH);  // the first tasks go to the groups in order
-  __syncthreads();
-  // members of each slot inside each wave's token range
-  unsigned long long same[kF3Chunks];
-  bool member[kF3Chunks];
-#pragma unroll
-  for (int k = 0; k < kF3Chunks; ++k) {
-    const int i = r0 + k * 64 + lane;
-    member[k] = slot_of[k] >= 0 && lds_kept[slot_of[k]] != i;
-    same[k] = same_slot_lanes(member[k], slot_of[k], nbits);
-    if (member[k] && (same[k] & ((1ull << lane) - 1)) == 0) tbl[slot_of[k] * NW + wave] += __popcll(same[k]);
-  }
-  __syncthreads();
-  TRACE(1);
-  int n_tasks, n_multi, n_copy;
-  {  // one packed scan over the slots (B <= 256 <= threads): member offsets, multi-task slots,
-     // their chunks, single-task slots and copy-only slots
-    const int slot = threadIdx.x;
-    int n = 0;
-    if (slot < s.B)
-      for (int w = 0; w < NW; ++w) n += tbl[slot * NW + w];
-    const int nt = (n + kUnitChunk - 1) / kUnitChunk;  // 0: copy, 1: one task, more: chunks + fold
-    const bool valid = slot < s.B;
-    const long long packed = (long long)n | ((long long)(valid && nt > 1) << 16) |
-                             ((long long)(nt > 1 ? nt : 0) << 24) | ((long long)(valid && nt == 1) << 36) |
-                             ((long long)(valid && nt == 0) << 48);
-    long long tot;
-    const long long ex = block_exclusive_scan<kF3Threads, long long>(packed, lds_wave, &tot);
-    const int sg = (int)(ex & 0xffff), mb = (int)((ex >> 16) & 0xff), pb = (int)((ex >> 24) & 0xfff),
-              sb = (int)((ex >> 36) & 0xfff), cb = (int)((ex >> 48) & 0xfff);
-    const int n_part = (int)((tot >> 24) & 0xfff);
-    n_multi = (int)((tot >> 16) & 0xff);
-    n_tasks = n_part + (int)((tot >> 36) & 0xfff);
-    n_copy = (int)((tot >> 48) & 0xfff);
-    if (valid) {
-      int base = sg;
-      for (int w = 0; w < NW; ++w) {
-        const int t = tbl[slot * NW + w];
-        tbl[slot * NW + w] = base;
-        base += t;
-      }
-      if (nt == 0) {
-        copies[cb] = slot;
-      } else if (nt == 1) {
-        tasks[n_part + sb] = make_int4(slot, sg, n, -1);  // after all the chunks of large slots
-      } else {
-        for (int j = 0; j < nt; ++j)
-          tasks[pb + j] = make_int4(slot, sg + j * kUnitChunk, min(kUnitChunk, n - j * kUnitChunk), pb + j);
-        multi[mb] = make_int4(slot, pb, nt, n);
-      }
-    }
-  }
-  __syncthreads();
-  TRACE(2);
-#pragma unroll
-  for (int k = 0; k < kF3Chunks; ++k) {
-    const unsigned long long below = same[k] & ((1ull << lane) - 1);
-    if (member[k]) {
-      const int cur = tbl[slot_of[k] * NW + wave];
-      members[cur + __popcll(below)] = r0 + k * 64 + lane;
-      if (below == 0) tbl[slot_of[k] * NW + wave] = cur + __popcll(same[k]);
-    }
-  }
-
-  const int rg = lane / LPR, ch = lane % LPR;
-  const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
-  const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + head_off;
-  const uint4 *V = reinterpret_cast<const uint4 *>(c.V) + head_off;
-  uint4 *Ko = reinterpret_cast<uint4 *>(c.K_out) + (unit * sh.SB + s.kept_off) * LPR;
-  uint4 *Vo = reinterpret_cast<uint4 *>(c.V_out) + (unit * sh.SB + s.kept_off) * LPR;
-  constexpr int kGroups = kF3Waves * RPL;
-  const int gid = wave * RPL + rg;
-
-  // pivots nobody merges into: bit copies (needs no member list, so it runs before the barrier)
-  for (int base = 0; base < n_copy; base += kGroups * U) {  // the U loads of a pass are independent
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int idx = base + u * kGroups + gid;
-      if (idx < n_copy) {
-        const int slot = copies[idx];
-        const int tok = lds_kept[slot];
-        const uint4 kc = K[(long long)tok * sh.ks_tok + ch];
-        const uint4 vc = V[(long long)tok * sh.ks_tok + ch];
-        Ko[(long long)slot * LPR + ch] = kc;
-        Vo[(long long)slot * LPR + ch] = vc;
-      }
-    }
-  }
-  __syncthreads();
-  TRACE(3);
-
-  // Every group works on its own task, one batch of U rows per trip of the loop, and takes the
-  // next free task when it is done (large chunks come first in the list), so neither a long
-  // task nor an unlucky share holds anybody up.  Who computes a task does not change its sum.
-  int q = gid;
-  bool have = q < n_tasks;
-  int4 task = have ? tasks[q] : make_int4(0, 0, 0, 0);
-  int j0 = 0;
-  float ak[EPC], av[EPC];
-#pragma unroll
-  for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
-  while (__any(have)) {
-    if (have) {
-      // rows of this task: the pivot itself first if the task finishes its slot, then the members
-      const int lead = task.w < 0 ? 1 : 0;
-      const int nrows = task.z + lead;
-      const int *mem = members + task.y - lead;
-      const int pivot_tok = lds_kept[task.x];
-      int tokv[U];
-      uint4 kc[U], vc[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int j = j0 + u;
-        tokv[u] = j < nrows ? (j < lead ? pivot_tok : mem[j]) : -1;
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (tokv[u] >= 0) {
-          kc[u] = K[(long long)tokv[u] * sh.ks_tok + ch];
-          vc[u] = V[(long long)tokv[u] * sh.ks_tok + ch];
-        }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (tokv[u] >= 0) {
-          float fk[EPC], fv[EPC];
-          chunk_to_floats<kBF16>(kc[u], fk);
-          chunk_to_floats<kBF16>(vc[u], fv);
-#pragma unroll
-          for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
-        }
-      j0 += U;
-      if (j0 >= nrows) {  // task finished: write its result, move to the next one of this group
-        if (lead) {
-          const float w = 1.0f / (float)(1 + task.z);  // uniform merge weight
-#pragma unroll
-          for (int e = 0; e < EPC; ++e) { ak[e] *= w; av[e] *= w; }
-          Ko[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(ak);
-          Vo[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(av);
-        } else {
-          float *pp = partials + (long long)task.w * 2 * D + ch * EPC;
-#pragma unroll
-          for (int e = 0; e < EPC; ++e) { pp[e] = ak[e]; pp[D + e] = av[e]; }
-        }
-        int nq = 0;
-        if (ch == 0) nq = atomicAdd(&sh_next, 1);
-        q = __shfl(nq, rg * LPR, 64);
-        have = q < n_tasks;
-        if (have) task = tasks[q];
-        j0 = 0;
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
-      }
-    }
-  }
-  TRACE(4);
-  __syncthreads();
-  TRACE(5);
-  // slots cut into several tasks: pivot row plus the partials in task order
-  for (int qm = wave; qm < n_multi; qm += kF3Waves) {
-    const int4 e4 = multi[qm];
-    const int pivot_tok = lds_kept[e4.x];
-    const float w = 1.0f / (float)(1 + e4.w);
-    if (lane < 2 * LPR) {
-      const int tensor = lane / LPR, cch = lane % LPR;
-      const uint4 *src = tensor ? V : K;
-      float acc[EPC];
-      chunk_to_floats<kBF16>(src[(long long)pivot_tok * sh.ks_tok + cch], acc);
-      for (int pi = 0; pi < e4.z; ++pi) {
-        const float *pp = partials + (long long)(e4.y + pi) * 2 * D + tensor * D + cch * EPC;
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) acc[e] += pp[e];
-      }
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[e] *= w;
-      (tensor ? Vo : Ko)[(long long)e4.x * LPR + cch] = floats_to_chunk<kBF16>(acc);
-    }
-  }
-  TRACE(6);
+  unit_merge_body<D, U>(c, s, unit, l, gkv, c.assign + unit * sh.T + s.tok_off, c.kept_idx + unit * sh.SB + s.kept_off,
+                        lds_i, maxB, maxE, lds_wave, &sh_next);
 }
 
 // ---- dispatch --------------------------------------------------------------------------------
@@ -829,7 +584,7 @@ hipError_t launch_plan_k(const Ctx &c, int b_pad, size_t lds) {
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_UNIT_PLAN);
-  unit_plan_kernel<D, RB, NT><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kPThreads, lds, c.stream>>>(c, b_pad);
+  unit_plan_kernel<D, RB, NT><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kPThreads, lds, c.stream>>>(c, b_pad);
   return hipGetLastError();
 }
 
@@ -857,28 +612,32 @@ hipError_t launch_f2(const Ctx &c) {
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_UNIT_MATCH);
-  unit_match_kernel<D><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kF2Threads, lds, c.stream>>>(c, b_pad);
+  unit_match_kernel<D><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kF2Threads, lds, c.stream>>>(c, b_pad);
   return hipGetLastError();
 }
 
-template <int D>
+template <int D, int U, bool FLOW>
 hipError_t launch_f3(const Ctx &c) {
-  const MergeLds lay = merge_lds_layout(c.sh.maxB, c.sh.maxE, D);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_merge_kernel<D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lay.total_bytes);
+  const int b_pad = (c.sh.maxB + 31) / 32 * 32;
+  size_t lds = (size_t)merge_lds_layout(c.sh.maxB, c.sh.maxE, D).total_bytes;
+  if (FLOW && match_lds_bytes(c.sh, b_pad) > lds) lds = match_lds_bytes(c.sh, b_pad);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_merge_kernel<D, U, FLOW>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  ProfScope ps(c.stream, KID_UNIT_MERGE);
-  unit_merge_kernel<D><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kF3Threads, lay.total_bytes, c.stream>>>(
-      c, c.sh.maxB, c.sh.maxE);
+  ProfScope ps(c.stream, FLOW ? KID_UNIT_FLOW_MERGE : KID_UNIT_MERGE);
+  unit_merge_kernel<D, U, FLOW><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kF3Threads, lds, c.stream>>>(
+      c, c.sh.maxB, c.sh.maxE, b_pad);
   return hipGetLastError();
 }
 
 }  // namespace
 
 #ifdef FLOWMM_TRACE
+}  // namespace flowmm
 extern "C" __attribute__((visibility("default"))) int flowmm_trace_set(void *p) {
-  return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p));
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(flowmm::g_trace), &p, sizeof(p));
 }
+namespace flowmm {
 #endif
 
 bool unit_path_fits(const Shape &sh) {
@@ -890,15 +649,31 @@ bool unit_path_fits(const Shape &sh) {
   return true;
 }
 
-hipError_t launch_unit_plan(const Ctx &c) {  // score + select + cross-modal match, then flow + intra-modal layers
+hipError_t launch_unit_flow_match(const Ctx &c) { return c.sh.d == 128 ? launch_f2<128>(c) : launch_f2<64>(c); }
+
+hipError_t launch_unit_plan(const Ctx &c, bool with_flow) {  // score + select + cross-modal match, then flow + intra-modal layers
   const int rb = c.sh.R_pad / 32;
   hipError_t e;
   if (c.sh.d == 128) e = rb == 1 ? launch_f1<128, 1>(c) : launch_f1<128, 2>(c);
   else e = rb == 1 ? launch_f1<64, 1>(c) : launch_f1<64, 2>(c);
-  if (e != hipSuccess) return e;
-  return c.sh.d == 128 ? launch_f2<128>(c) : launch_f2<64>(c);
+  if (e != hipSuccess || !with_flow) return e;
+  return launch_unit_flow_match(c);
 }
 
-hipError_t launch_unit_merge(const Ctx &c) { return c.sh.d == 128 ? launch_f3<128>(c) : launch_f3<64>(c); }
+// with_flow: the launch also settles the layer strategies and rematches the intra-modal layers
+// (then it takes the place of launch_unit_flow_match + launch_unit_merge after the plan kernel)
+hipError_t launch_unit_merge(const Ctx &c, bool with_flow) {
+  // Rows in flight per lane group: with four workgroups on every compute unit the kernel is bound
+  // by memory bandwidth and more than two rows in flight only lengthen the queues (measured: 80 us
+  // with 2, 102 us with 8 on 1024 units); a grid that leaves compute units short of workgroups is
+  // bound by latency and wants many (20 us instead of 40 us per workgroup).
+  const bool many = (long long)c.sh.batch * c.sh.Hkv * c.layers >= 4 * 256;
+  if (c.sh.d == 128) {
+    if (many) return with_flow ? launch_f3<128, 2, true>(c) : launch_f3<128, 2, false>(c);
+    return with_flow ? launch_f3<128, 8, true>(c) : launch_f3<128, 8, false>(c);
+  }
+  if (many) return with_flow ? launch_f3<64, 2, true>(c) : launch_f3<64, 2, false>(c);
+  return with_flow ? launch_f3<64, 8, true>(c) : launch_f3<64, 8, false>(c);
+}
 
 }  // namespace flowmm

@@ -19,16 +19,20 @@ def upload(wl, device="cuda:0", layers=None):
     return fb.upload_workload(wl, device, layers)
 
 
-def run_gpu(wl, theta=None, tau=None, device="cuda:0", tensors=None, flags=0):
-    """Run flowmm_plan + flowmm_merge through the C ABI; returns numpy copies of everything."""
+def run_gpu(wl, theta=None, tau=None, device="cuda:0", tensors=None, flags=0, fused=False):
+    """Run flowmm_plan + flowmm_merge (or the one-call flowmm_plan_merge) through the C ABI;
+    returns numpy copies of everything."""
     import torch
     from paper_2511_05534_amd import binding as fb
     params = fb.Params.from_workload(wl, theta=theta, tau=tau, flags=flags)
     K, V, Q = tensors if tensors is not None else upload(wl, device)
     bufs = fb.DeviceBuffers(params, device)
     stream = torch.cuda.current_stream().cuda_stream
-    bufs.plan(K, Q, stream)
-    bufs.merge(K, V, stream)
+    if fused:
+        bufs.plan_merge(K, V, Q, stream)
+    else:
+        bufs.plan(K, Q, stream)
+        bufs.merge(K, V, stream)
     torch.cuda.synchronize()
     out = {n: getattr(bufs, n).cpu().numpy() for n in fb.PLAN_FIELDS}
     out["K_out"] = bufs.K_out.float().cpu().numpy()

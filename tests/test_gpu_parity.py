@@ -43,14 +43,15 @@ SMALL_CASES = {
 }
 
 
-@pytest.mark.parametrize("path", ["auto", "generic"])
+@pytest.mark.parametrize("path", ["auto", "generic", "fused"])
 @pytest.mark.parametrize("name", list(SMALL_CASES))
 def test_small_cases_match_oracle(oracle, name, path):
     """`auto` lets the library pick (short bf16 prompts take the unit-resident kernels); `generic`
-    forces the multi-workgroup kernels on the same inputs."""
+    forces the multi-workgroup kernels on the same inputs; `fused` is the one-call entry point
+    (short bf16 prompts take the streaming kernel that merges right after matching)."""
     w = small(name, **SMALL_CASES[name])
     print(f"case {name} [{path}]: L={w.seqlens} B={w.budgets} dtype={w.dtype}", flush=True)
-    gpu = run_gpu(w, flags=0 if path == "auto" else 1)
+    gpu = run_gpu(w, flags=1 if path == "generic" else 0, fused=path == "fused")
     rep = Report()
     for l in range(w.n_layers):
         check_layer(oracle, w, gpu, l, report=rep)
@@ -69,6 +70,25 @@ def test_both_paths_agree_on_decisions():
     agree = (a["assign"] == b["assign"]).mean()
     assert agree > 0.995, agree
     assert (a["mode"] == b["mode"]).all()
+
+
+def test_one_call_equals_two_calls():
+    """flowmm_plan_merge against flowmm_plan + flowmm_merge: the same decisions up to the last bits of
+    the importances (the two spread the key tiles over their waves differently), and bit-identical
+    merged rows wherever the decisions are the same (both merge alike)."""
+    for theta in (0.25, 2.0):
+        w = small("onecall", Hq=4, Hkv=2, spans=((35, 576, 64),), pct=(10,), n_layers=3, theta=theta)
+        a = run_gpu(w)
+        b = run_gpu(w, fused=True)
+        assert np.allclose(a["importance"], b["importance"], rtol=1e-5, atol=0)
+        assert (a["mode"] == b["mode"]).all() and np.allclose(a["rho"], b["rho"], rtol=1e-5, atol=0)
+        agree = (a["assign"] == b["assign"]).mean()
+        assert agree > 0.995, agree
+        same = (a["assign"] == b["assign"]).all(axis=-1) & (a["kept_idx"] == b["kept_idx"]).all(axis=-1)
+        assert (a["K_out"][same] == b["K_out"][same]).all() and (a["V_out"][same] == b["V_out"][same]).all()
+        c = run_gpu(w, fused=True)
+        for k in b:
+            assert (b[k] == c[k]).all() or np.array_equal(b[k], c[k], equal_nan=True), k
 
 
 def test_config1_generic_path_sampled(oracle):
@@ -156,16 +176,18 @@ def test_ragged_batch_equals_each_sequence_alone():
         assert (alone["rho"][:, 0] == full["rho"][:, b]).all()
 
 
-@pytest.mark.parametrize("cfg,n_layers,sample", [
-    (1, 32, [(0, [0, 17]), (31, [5])]),      # the benchmark configuration, full depth (unit-resident kernels)
-    (2, 2, [(1, [0, 3])]),
-    (3, 2, [(0, [2])]),
-    (4, 2, [(1, [1])]),
+@pytest.mark.parametrize("cfg,n_layers,sample,fused", [
+    (1, 32, [(0, [0, 17]), (31, [5])], True),   # the benchmark configuration, full depth, as bench.py runs it
+    (1, 32, [(0, [0, 17]), (31, [5])], False),  # the same through the two calls (unit-resident kernels)
+    (2, 2, [(1, [0, 3])], False),
+    (3, 2, [(0, [2])], False),
+    (4, 2, [(1, [1])], False),
+    (2, 2, [(0, [1])], True),
 ])
-def test_benchmark_configs_sampled_units(oracle, cfg, n_layers, sample):
+def test_benchmark_configs_sampled_units(oracle, cfg, n_layers, sample, fused):
     w = wl.config(cfg, n_layers=n_layers)
-    print(f"config {cfg}: {w.name} layers={n_layers} T={w.total_tokens}", flush=True)
-    gpu = run_gpu(w)
+    print(f"config {cfg}: {w.name} layers={n_layers} T={w.total_tokens} fused={fused}", flush=True)
+    gpu = run_gpu(w, fused=fused)
     rep = Report()
     for layer, heads in sample:
         seqs = None if w.batch == 1 else [0, w.batch - 1]
