@@ -25,7 +25,7 @@ namespace {
 constexpr bool kBF16 = true;
 
 // ============================ score + select + match (cross-modal) ===========================
-// One workgroup of eight waves per unit.  Wave w keeps the key tiles w, w+8, ... (32 keys each) in
+// One workgroup of WAVES (eight or twelve) waves per unit.  Wave w keeps the key tiles w, w+WAVES, ... (32 keys each) in
 // registers for the whole kernel, in the layout every contraction here uses, so K is read from
 // HBM once.  The logits are computed twice from those registers: once for the row statistics,
 // once for the normalised column sums.  The pivots' rows go from the registers of the lanes that
@@ -34,8 +34,7 @@ constexpr bool kBF16 = true;
 // the wave.  The layer's strategy needs all its query heads and is not known here: this kernel
 // matches as a cross-modal layer does; unit_match_kernel then settles the strategy and redoes the
 // intra-modal layers.
-constexpr int kPThreads = 512;
-constexpr int kPWaves = kPThreads / 64;
+constexpr int kPMaxWaves = 12;  // workgroups of 8 or 12 waves (12 * 154 registers still fit a compute unit)
 
 struct PlanLds {  // byte offsets into the dynamic LDS block
   int q, stat, cval, rowimg, cross, keys, assign, kept, piv, w, bias, total_bytes;
@@ -46,7 +45,7 @@ __host__ __device__ inline PlanLds plan_lds_layout(int rows, int b_pad, int nch)
   int off = 0;
   m.q = off; off += rows * (nch + 1) * 16;
   m.piv = off; off += b_pad * (nch + 1) * 16;
-  m.stat = off; off += kPWaves * rows * 8;
+  m.stat = off; off += kPMaxWaves * rows * 8;
   m.cval = off; off += rows * 4;
   m.rowimg = off; off += rows * 4;
   m.cross = off; off += 32 * 2 * 4;
@@ -59,8 +58,9 @@ __host__ __device__ inline PlanLds plan_lds_layout(int rows, int b_pad, int nch)
   return m;
 }
 
-template <int D, int RB, int NT>
-__global__ __launch_bounds__(kPThreads) void unit_plan_kernel(Ctx c, int b_pad) {
+template <int D, int RB, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad) {
+  constexpr int kPThreads = WAVES * 64, kPWaves = WAVES;
   using CF = Cfg<kBF16, D>;
   constexpr int NCH = CF::NCH, NF = CF::NF, RS = NCH + 1;
   constexpr int ROWS = RB * 32;
@@ -578,13 +578,13 @@ size_t plan_lds_bytes(const Shape &sh, int b_pad) {
   return (size_t)plan_lds_layout(sh.R_pad, b_pad, sh.d * 2 / 16).total_bytes;
 }
 
-template <int D, int RB, int NT>
+template <int D, int RB, int NT, int WAVES>
 hipError_t launch_plan_k(const Ctx &c, int b_pad, size_t lds) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_plan_kernel<D, RB, NT>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_plan_kernel<D, RB, NT, WAVES>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_UNIT_PLAN);
-  unit_plan_kernel<D, RB, NT><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kPThreads, lds, c.stream>>>(c, b_pad);
+  unit_plan_kernel<D, RB, NT, WAVES><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), WAVES * 64, lds, c.stream>>>(c, b_pad);
   return hipGetLastError();
 }
 
@@ -592,12 +592,15 @@ template <int D, int RB>
 hipError_t launch_f1(const Ctx &c) {
   const int b_pad = (c.sh.maxB + 31) / 32 * 32;
   const size_t lds = plan_lds_bytes(c.sh, b_pad);
-  switch (((c.sh.maxL + 31) / 32 + kPWaves - 1) / kPWaves) {  // tiles per wave
-    case 1: return launch_plan_k<D, RB, 1>(c, b_pad, lds);
-    case 2: return launch_plan_k<D, RB, 2>(c, b_pad, lds);
-    case 3: return launch_plan_k<D, RB, 3>(c, b_pad, lds);
-    default: return launch_plan_k<D, RB, 4>(c, b_pad, lds);
-  }
+  // Key tiles per wave and waves per workgroup: the unit's keys must fit the registers of one
+  // workgroup, and twelve waves with two tiles each need fewer registers per wave (three waves per
+  // SIMD) than eight waves with three.
+  const int tiles = (c.sh.maxL + 31) / 32;
+  if (tiles <= 8) return launch_plan_k<D, RB, 1, 8>(c, b_pad, lds);
+  if (tiles <= 12) return launch_plan_k<D, RB, 1, 12>(c, b_pad, lds);
+  if (tiles <= 16) return launch_plan_k<D, RB, 2, 8>(c, b_pad, lds);
+  if (tiles <= 24) return launch_plan_k<D, RB, 2, 12>(c, b_pad, lds);
+  return launch_plan_k<D, RB, 4, 8>(c, b_pad, lds);
 }
 
 size_t match_lds_bytes(const Shape &sh, int b_pad) {

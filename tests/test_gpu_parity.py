@@ -173,7 +173,9 @@ def test_ragged_batch_equals_each_sequence_alone():
         assert (alone["kept_idx"] == full["kept_idx"][:, :, cuk[b]:cuk[b + 1]]).all()
         assert (alone["K_out"] == full["K_out"][:, :, cuk[b]:cuk[b + 1]]).all()
         assert (alone["V_out"] == full["V_out"][:, :, cuk[b]:cuk[b + 1]]).all()
-        assert (alone["rho"][:, 0] == full["rho"][:, b]).all()
+        # the workgroup shape follows the longest sequence of the call, and with it the order in which the
+        # row statistics of the softmax are folded: the last bits of rho may differ
+        assert np.allclose(alone["rho"][:, 0], full["rho"][:, b], rtol=1e-5, atol=0)
 
 
 @pytest.mark.parametrize("cfg,n_layers,sample,fused", [
