@@ -26,6 +26,14 @@
  *   fmo_merge  - fold every matched non-pivot K/V row into its pivot by a
  *                uniform mean (the paper leaves f_merge/g_merge open; uniform
  *                weights are this build's reading).
+ *
+ * Variants of the paper's ablation study (Effectiveness of Each Component), same stages:
+ *   fmo_flow with invert != 0 - the strategy misaligned with the measured flow
+ *                (cross-modal merging exactly where the rule says intra-modal);
+ *   fmo_merge_weighted        - f_merge/g_merge as a similarity-weighted mean: the pivot
+ *                counts 1, a member counts max(u, 0) with u its cosine to the pivot.
+ *   ("Without sensitivity-adaptive matching" is tau = +inf; "without information flow
+ *   guidance" is a theta below 0 or above 1; neither needs code of its own.)
  */
 #include <math.h>
 #include <stdint.h>
@@ -87,12 +95,14 @@ void fmo_score(int Hq, int Hkv, int L, int W, int d, double scale, const float *
   }
 }
 
-/* rho = mean of the per-head shares; returns 1 (cross-modal) iff rho > theta. */
-int fmo_flow(int Hq, const double *cross, double theta, double *rho) {
+/* rho = mean of the per-head shares; returns 1 (cross-modal) iff rho > theta.
+ * invert != 0 gives the misaligned strategy: 1 iff NOT rho > theta. */
+int fmo_flow(int Hq, const double *cross, double theta, int invert, double *rho) {
   double s = 0.0;
   for (int h = 0; h < Hq; ++h) s += cross[h];
   *rho = s / (double)Hq;
-  return (*rho > theta) ? 1 : 0;
+  const int cross_modal = (*rho > theta) ? 1 : 0;
+  return invert ? 1 - cross_modal : cross_modal;
 }
 
 /* One KV head.  The last W positions are forced pivots; the remaining B-W pivots
@@ -199,6 +209,47 @@ void fmo_merge(int L, int d, int B, const float *K, const float *V, const int32_
   }
 }
 
+/* Similarity-weighted variant of fmo_merge:
+ *   out[s] = (row[pivot] + sum_i w_i row[i]) / (1 + sum_i w_i),  w_i = max(u_i, 0),
+ * u_i the cosine between member key i and the pivot key (0 if either is a zero row); V rows take
+ * the weights of their K rows.  wsum [B] receives 1 + sum_i w_i. */
+void fmo_merge_weighted(int L, int d, int B, const float *K, const float *V, const int32_t *kept_idx,
+                        const int32_t *assign, double *Kout, double *Vout, int32_t *n_members, double *wsum) {
+  for (int s = 0; s < B; ++s) {
+    n_members[s] = 0;
+    wsum[s] = 1.0;
+    for (int c = 0; c < d; ++c) {
+      Kout[(size_t)s * d + c] = (double)K[(size_t)kept_idx[s] * d + c];
+      Vout[(size_t)s * d + c] = (double)V[(size_t)kept_idx[s] * d + c];
+    }
+  }
+  for (int i = 0; i < L; ++i) {
+    const int s = assign[i];
+    if (s < 0 || kept_idx[s] == i) continue;
+    const float *ki = K + (size_t)i * d, *kj = K + (size_t)kept_idx[s] * d;
+    double dot = 0.0, ni = 0.0, nj = 0.0;
+    for (int c = 0; c < d; ++c) {
+      dot += (double)ki[c] * (double)kj[c];
+      ni += (double)ki[c] * (double)ki[c];
+      nj += (double)kj[c] * (double)kj[c];
+    }
+    double w = (ni > 0.0 && nj > 0.0) ? dot / (sqrt(ni) * sqrt(nj)) : 0.0;
+    if (w < 0.0) w = 0.0;
+    n_members[s] += 1;
+    wsum[s] += w;
+    for (int c = 0; c < d; ++c) {
+      Kout[(size_t)s * d + c] += w * (double)K[(size_t)i * d + c];
+      Vout[(size_t)s * d + c] += w * (double)V[(size_t)i * d + c];
+    }
+  }
+  for (int s = 0; s < B; ++s) {
+    for (int c = 0; c < d; ++c) {
+      Kout[(size_t)s * d + c] /= wsum[s];
+      Vout[(size_t)s * d + c] /= wsum[s];
+    }
+  }
+}
+
 /* Round-to-nearest-even of doubles to the output dtype (0 = fp32, 1 = bf16), result as float. */
 void fmo_round(int64_t n, int dtype, const double *x, float *y) {
   for (int64_t i = 0; i < n; ++i) {
@@ -225,7 +276,7 @@ void fmo_layer(int Hq, int Hkv, int L, int W, int d, int B, int dtype, double sc
                int32_t *n_dropped, float *Kout, float *Vout) {
   double *cross = (double *)malloc(sizeof(double) * (size_t)Hq);
   fmo_score(Hq, Hkv, L, W, d, scale, K, Q, mod, I, cross);
-  *mode = fmo_flow(Hq, cross, theta, rho);
+  *mode = fmo_flow(Hq, cross, theta, 0, rho);
   free(cross);
   const int mode_cross = *mode;
 #pragma omp parallel for schedule(dynamic, 1)

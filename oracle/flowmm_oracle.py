@@ -75,11 +75,11 @@ def score(K, Q, mod, scale=None):
     return I, cross
 
 
-def flow(cross, theta):
-    """-> (rho, mode) with mode 1 = cross-modal merging, 0 = intra-modal."""
+def flow(cross, theta, invert=False):
+    """-> (rho, mode) with mode 1 = cross-modal merging, 0 = intra-modal; invert: the misaligned rule."""
     cross = _f64(cross)
     rho = C.c_double(0.0)
-    mode = _load().fmo_flow(len(cross), _p(cross, C.c_double), C.c_double(theta), C.byref(rho))
+    mode = _load().fmo_flow(len(cross), _p(cross, C.c_double), C.c_double(theta), int(bool(invert)), C.byref(rho))
     return float(rho.value), int(mode)
 
 
@@ -119,6 +119,21 @@ def merge(K, V, kept_idx, assign):
                       _p(assign, C.c_int32), _p(ko, C.c_double), _p(vo, C.c_double),
                       _p(nm, C.c_int32))
     return ko, vo, nm
+
+
+def merge_weighted(K, V, kept_idx, assign):
+    """Similarity-weighted merge: K, V [L][d] -> Kout, Vout [B][d] float64, n_members [B], wsum [B]."""
+    K, V, kept_idx, assign = _f32(K), _f32(V), _i32(kept_idx), _i32(assign)
+    L, d = K.shape
+    B = len(kept_idx)
+    ko = np.empty((B, d), dtype=np.float64)
+    vo = np.empty((B, d), dtype=np.float64)
+    nm = np.empty(B, dtype=np.int32)
+    ws = np.empty(B, dtype=np.float64)
+    _load().fmo_merge_weighted(L, d, B, _p(K, C.c_float), _p(V, C.c_float), _p(kept_idx, C.c_int32),
+                               _p(assign, C.c_int32), _p(ko, C.c_double), _p(vo, C.c_double),
+                               _p(nm, C.c_int32), _p(ws, C.c_double))
+    return ko, vo, nm, ws
 
 
 def round_output(x, dtype: str):

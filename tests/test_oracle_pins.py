@@ -343,6 +343,84 @@ def test_merge_full_budget_and_pure_eviction_are_bit_exact(oracle):
     assert (ko == K[0][kept]).all() and (vo == V[0][kept]).all() and nd == 22
 
 
+# --------------------------------------------------------------------------------------
+# variants of the ablation study: misaligned strategy, similarity-weighted merge
+# --------------------------------------------------------------------------------------
+def test_inverted_flow_is_the_opposite_strategy(oracle):
+    cross = np.array([0.1, 0.5, 0.3, 0.7])  # mean 0.4
+    for theta in (0.25, 0.4, 0.55, -1.0, 2.0):  # 0.4: rho == theta is intra-modal, so its inverse is cross
+        rho, mode = oracle.flow(cross, theta)
+        rho_i, mode_i = oracle.flow(cross, theta, invert=True)
+        assert rho == rho_i == pytest.approx(0.4)
+        assert mode == (1 if 0.4 > theta else 0) and mode_i == 1 - mode
+
+
+def np_merge_weighted(K, V, kept, assign):
+    """Dense restatement: a [B x L] weight matrix (1 on the pivot, max(cos, 0) on members), rows normalised."""
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    L, B = len(K), len(kept)
+    Wm = np.zeros((B, L))
+    norms = np.linalg.norm(K64, axis=1)
+    for i in range(L):
+        s = assign[i]
+        if s < 0:
+            continue
+        j = kept[s]
+        if i == j:
+            Wm[s, i] = 1.0
+        elif norms[i] > 0 and norms[j] > 0:
+            Wm[s, i] = max(K64[i] @ K64[j] / (norms[i] * norms[j]), 0.0)
+    tot = Wm.sum(axis=1, keepdims=True)
+    return (Wm / tot) @ K64, (Wm / tot) @ V64, tot[:, 0]
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_weighted_merge_matches_dense_weight_matrix(oracle, seed):
+    K, V, Q, mod = rand_case(seed + 60, L=48, W=4)
+    I, _ = oracle.score(K, Q, mod)
+    kept = oracle.select(I[0], 4, 9)
+    assign, nd = oracle.match(K[0], I[0], kept, mod, 1, float(np.sort(I[0][kept])[-3]))
+    ko, vo, nm, ws = oracle.merge_weighted(K[0], V[0], kept, assign)
+    ko_np, vo_np, ws_np = np_merge_weighted(K[0], V[0], kept, assign)
+    np.testing.assert_allclose(ko, ko_np, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(vo, vo_np, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(ws, ws_np, rtol=1e-13)
+    _, _, nm_u = oracle.merge(K[0], V[0], kept, assign)
+    assert nm.tolist() == nm_u.tolist()
+    assert (ws >= 1.0).all() and (ws <= 1.0 + nm + 1e-12).all()  # every weight lies in [0, 1]
+
+
+def test_weighted_merge_special_cases(oracle):
+    rng = np.random.default_rng(7)
+    d = 16
+    pivot = rng.standard_normal(d).astype(np.float32)
+    ortho = rng.standard_normal(d)
+    ortho -= (ortho @ pivot) / (pivot @ pivot) * pivot
+    K = np.stack([pivot, 2 * pivot, 0.5 * pivot, -pivot, np.zeros(d, np.float32),
+                  ortho.astype(np.float32), rng.standard_normal(d).astype(np.float32)]).astype(np.float32)
+    V = rng.standard_normal(K.shape).astype(np.float32)
+    kept = np.array([0, 6], dtype=np.int32)
+    # positive multiples of the pivot weigh 1: the plain mean of rows 0, 1, 2
+    assign = np.array([0, 0, 0, -1, -1, -1, 1], dtype=np.int32)
+    ko, vo, nm, ws = oracle.merge_weighted(K, V, kept, assign)
+    ku, vu, _ = oracle.merge(K, V, kept, assign)
+    np.testing.assert_allclose(ko, ku, rtol=1e-12)
+    np.testing.assert_allclose(vo, vu, rtol=1e-12)
+    assert ws[0] == pytest.approx(3.0) and ws[1] == 1.0
+    # an opposite, a zero and an orthogonal key weigh 0 (up to the rounding of the orthogonal one): the pivot stays
+    assign = np.array([0, -1, -1, 0, 0, 0, 1], dtype=np.int32)
+    ko, vo, nm, ws = oracle.merge_weighted(K, V, kept, assign)
+    assert nm[0] == 3 and ws[0] == pytest.approx(1.0, abs=1e-6)
+    np.testing.assert_allclose(ko[0], K[0], atol=1e-6)
+    np.testing.assert_allclose(vo[0], V[0], atol=1e-5)
+    assert (ko[1] == K[6]).all() and (vo[1] == V[6]).all()
+    # weights of a slot sum to one: its merged key lies between the smallest and largest member entry
+    assign = np.array([0, 0, 0, 0, 0, 0, 0], dtype=np.int32)
+    kept1 = np.array([0], dtype=np.int32)
+    ko, vo, nm, ws = oracle.merge_weighted(K, V, kept1, assign)
+    assert (ko[0] <= K.max(axis=0) + 1e-12).all() and (ko[0] >= K.min(axis=0) - 1e-12).all()
+
+
 def test_rounding_to_bf16_is_nearest_even(oracle):
     # bf16 has 8 significant bits: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0)
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -30, -3.0, 0.0,
