@@ -54,6 +54,18 @@ enum { FLOWMM_MODE_INTRA = 0, FLOWMM_MODE_CROSS = 1 };
  * sends them through the general multi-workgroup kernels instead (same results up to fp32
  * summation order; used by tests). */
 enum { FLOWMM_FLAG_GENERIC_PATH = 1 };
+/* Variants of the paper's component ablation (Effectiveness of Each Component), on the same
+ * kernels.  Two of them need no flag: "without sensitivity-adaptive matching" is tau = +inf, and
+ * "without information flow guidance" is a theta below 0 (always cross-modal) or above 1 (always
+ * intra-modal).
+ *   FLOWMM_FLAG_INVERT_FLOW    the strategy misaligned with the measured flow: a layer merges
+ *                              cross-modally iff NOT rho > theta (mode reports what was done).
+ *   FLOWMM_FLAG_WEIGHTED_MERGE f_merge / g_merge as a similarity-weighted mean:
+ *                              out[slot] = (row[pivot] + sum_i w_i row[i]) / (1 + sum_i w_i),
+ *                              w_i = max(u_i, 0), u_i the cosine between the keys of member i and
+ *                              of the pivot (0 if either is a zero row); V rows take the weights
+ *                              of their K rows.  Read by flowmm_merge and flowmm_plan_merge. */
+enum { FLOWMM_FLAG_INVERT_FLOW = 2, FLOWMM_FLAG_WEIGHTED_MERGE = 4 };
 
 /* Half-open token range [begin, end) local to its sequence, with its modality. */
 typedef struct {

@@ -16,7 +16,7 @@ from . import build as _build
 
 FLOWMM_OK, FLOWMM_EINVAL, FLOWMM_EUNSUPPORTED, FLOWMM_EWORKSPACE, FLOWMM_EHIP = range(5)
 FLOWMM_F32, FLOWMM_BF16 = 0, 1
-FLOWMM_FLAG_GENERIC_PATH = 1
+FLOWMM_FLAG_GENERIC_PATH, FLOWMM_FLAG_INVERT_FLOW, FLOWMM_FLAG_WEIGHTED_MERGE = 1, 2, 4
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
 EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_last_error",

@@ -55,7 +55,8 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   if (p->window < 1) return fail(FLOWMM_EINVAL, "window must be >= 1");
   if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return fail(FLOWMM_EINVAL, "scale must be finite and >= 0");
   if (std::isnan(p->theta)) return fail(FLOWMM_EINVAL, "theta is NaN");
-  if (p->flags & ~FLOWMM_FLAG_GENERIC_PATH) return fail(FLOWMM_EINVAL, "unknown bits in flags");
+  if (p->flags & ~(FLOWMM_FLAG_GENERIC_PATH | FLOWMM_FLAG_INVERT_FLOW | FLOWMM_FLAG_WEIGHTED_MERGE))
+    return fail(FLOWMM_EINVAL, "unknown bits in flags");
   if (p->cu_seqlens[0] != 0 || p->cu_spans[0] != 0) return fail(FLOWMM_EINVAL, "cu_seqlens[0] and cu_spans[0] must be 0");
 
   const int es = p->dtype == FLOWMM_BF16 ? 2 : 4;
@@ -76,6 +77,8 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->head_dim);
   sh.scale_log2e = scale * 1.4426950408889634f;
   sh.theta = p->theta;
+  sh.invert_flow = (p->flags & FLOWMM_FLAG_INVERT_FLOW) != 0;
+  sh.weighted_merge = (p->flags & FLOWMM_FLAG_WEIGHTED_MERGE) != 0;
   sh.ks_layer = p->k_stride_layer / epc; sh.ks_head = p->k_stride_head / epc; sh.ks_tok = p->k_stride_token / epc;
   sh.qs_layer = p->q_stride_layer / epc; sh.qs_head = p->q_stride_head / epc; sh.qs_tok = p->q_stride_token / epc;
 
@@ -212,6 +215,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   rg.multi = off; off += align256((size_t)units * sh.multi_total * sizeof(int4));
   rg.n_multi = off; off += align256((size_t)units * batch * 4);
   rg.partials = off; off += align256((size_t)units * sh.part_total * 2 * sh.d * 4);
+  rg.partial_w = off; off += align256((size_t)units * sh.part_total * 4);
   rg.merge_end = off;
   lo.workspace_bytes = rg.plan_end > rg.merge_end ? rg.plan_end : rg.merge_end;
 
@@ -268,6 +272,7 @@ void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *w
   c.multi = reinterpret_cast<int4 *>(ws + lo.rg.multi);
   c.n_multi = reinterpret_cast<int *>(ws + lo.rg.n_multi);
   c.partials = reinterpret_cast<float *>(ws + lo.rg.partials);
+  c.partial_w = reinterpret_cast<float *>(ws + lo.rg.partial_w);
 }
 
 flowmm_status hip_fail(hipError_t e, const char *what) {

@@ -39,6 +39,7 @@ struct Ctx {
   int4 *multi;         // [Lyr][Hkv][multi_total]         (slot, first partial, number of partials, members)
   int *n_multi;        // [Lyr][Hkv][batch]
   float *partials;     // [Lyr][Hkv][part_total][2][d]    fp32 partial row sums of K and V
+  float *partial_w;    // [Lyr][Hkv][part_total]          weight sums of those partials (weighted merge)
 };
 
 constexpr int kMetaChunkWords = 960;

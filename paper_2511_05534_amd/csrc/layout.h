@@ -57,6 +57,8 @@ struct Shape {
   int n_layers, Hq, Hkv, G, d, bf16;
   int batch, T, SB, W, W_pad, R_pad, maxB, maxL, maxE, n_spans;
   int unit_path;  // 1: every unit is handled by one workgroup (unit_path.hip)
+  int invert_flow;     // 1: the misaligned strategy (cross-modal merging iff NOT rho > theta)
+  int weighted_merge;  // 1: similarity-weighted mean instead of the uniform one
   int SBP;        // sum over sequences of the budget rounded up to a multiple of 32
   int tiles_score, tiles_match, tasks_total, multi_total, part_total;
   float scale_log2e, theta;
@@ -82,7 +84,7 @@ struct Regions {
   size_t meta, mod, cls_order;                              // both calls
   size_t part_stats, rowstat, cross_part;                   // plan: score
   size_t pl_slot, pl_tok, pl_w, pl_n, pack;                 // plan: match
-  size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials;  // merge
+  size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials, partial_w;  // merge
   size_t plan_end, merge_end;
 };
 

@@ -1,7 +1,9 @@
 // Step "merge": fold every matched non-pivot K/V row into its pivot,
 //   out[slot] = (row[pivot] + sum of member rows) / (1 + number of members),
 // the uniform-weight instance of the paper's K_merged = f_merge(K, S), V_merged = g_merge(V, S)
-// (FlowMM, Preliminary), writing a compacted cache in ascending pivot position.
+// (FlowMM, Preliminary), writing a compacted cache in ascending pivot position.  On request the
+// similarity-weighted mean instead (pivot weight 1, member weight max(cosine to the pivot's key, 0),
+// computed here from the rows being merged): the variant of the paper's component ablation.
 //
 // Three kernels, no floating-point atomics, so results are bit-identical from run to run:
 //   1. csr   : one workgroup per (sequence, kv head, layer) groups the evicted tokens by slot,
@@ -156,7 +158,9 @@ __global__ __launch_bounds__(kCsrThreads) void merge_csr_kernel(Ctx c, int nw_sh
   }
 }
 
-template <bool BF16, int D>
+// WEIGHTED: the similarity-weighted mean (the pivot counts 1, a member max(u, 0), u the cosine of
+// its key to the pivot's key, 0 for a zero row; V rows take the weights of their K rows).
+template <bool BF16, int D, bool WEIGHTED>
 __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
   using CF = Cfg<BF16, D>;
   constexpr int LPR = CF::NCH;        // lanes that cover one row
@@ -187,8 +191,23 @@ __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
   for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
   const bool single = task.w < 0;
   const int pivot_tok = c.kept_idx[unit * sh.SB + s.kept_off + task.x];
+  float wsum = 0.f;        // weighted merge: weights this row group has added
+  float pk[EPC], pss = 0.f;  // weighted merge: this lane's chunk of the pivot's key, its squared norm
+  if constexpr (WEIGHTED) {
+    chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], pk);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) pss = fmaf(pk[e], pk[e], pss);
+#pragma unroll
+    for (int o = LPR / 2; o >= 1; o >>= 1) pss += __shfl_xor(pss, o, 64);
+  }
   if (single && rg == 0) {
-    chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], ak);
+    if constexpr (WEIGHTED) {
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) ak[e] = pk[e];
+      wsum = 1.f;
+    } else {
+      chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], ak);
+    }
     chunk_to_floats<BF16>(V[(long long)pivot_tok * sh.ks_tok + ch], av);
   }
   for (int j0 = rg; j0 < task.z; j0 += RPL * U) {
@@ -208,10 +227,27 @@ __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (tokv[u] >= 0) {
-        float fk[EPC], fv[EPC];
+      // every lane takes part in the exchanges below, so rows past the end count as zero rows
+      float fk[EPC], fv[EPC];
+      const bool real = tokv[u] >= 0;
+      if (real) {
         chunk_to_floats<BF16>(kc[u], fk);
         chunk_to_floats<BF16>(vc[u], fv);
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) fk[e] = fv[e] = 0.f;
+      }
+      if constexpr (WEIGHTED) {
+        float dot = 0.f, ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) { dot = fmaf(fk[e], pk[e], dot); ss = fmaf(fk[e], fk[e], ss); }
+#pragma unroll
+        for (int o = LPR / 2; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o, 64); ss += __shfl_xor(ss, o, 64); }
+        const float w = ss > 0.f && pss > 0.f ? fmaxf(dot / (sqrtf(ss) * sqrtf(pss)), 0.f) : 0.f;
+        wsum += w;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) { ak[e] = fmaf(w, fk[e], ak[e]); av[e] = fmaf(w, fv[e], av[e]); }
+      } else if (real) {
 #pragma unroll
         for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
       }
@@ -225,10 +261,11 @@ __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
       ak[e] += __shfl_xor(ak[e], o, 64);
       av[e] += __shfl_xor(av[e], o, 64);
     }
+    if constexpr (WEIGHTED) wsum += __shfl_xor(wsum, o, 64);
   }
   if (rg != 0) return;
   if (single) {
-    const float den = (float)(1 + task.z);
+    const float den = WEIGHTED ? wsum : (float)(1 + task.z);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) { ak[e] = ak[e] / den; av[e] = av[e] / den; }
     const long long orow = (unit * sh.SB + s.kept_off + task.x) * LPR + ch;
@@ -241,11 +278,12 @@ __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
       *reinterpret_cast<float4 *>(p + e) = make_float4(ak[e], ak[e + 1], ak[e + 2], ak[e + 3]);
       *reinterpret_cast<float4 *>(p + D + e) = make_float4(av[e], av[e + 1], av[e + 2], av[e + 3]);
     }
+    if (WEIGHTED && ch == 0) c.partial_w[unit * sh.part_total + task.w] = wsum;
   }
 }
 
 // kFoldGroups workgroups per (sequence, kv head, layer) walk over its split slots, one wave per slot
-template <bool BF16, int D>
+template <bool BF16, int D, bool WEIGHTED>
 __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
   constexpr int EPC = Cfg<BF16, D>::kElemsPerChunk;
   constexpr int NCH = Cfg<BF16, D>::NCH;
@@ -264,7 +302,11 @@ __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
     const int pivot_tok = c.kept_idx[unit * sh.SB + s.kept_off + e4.x];
     const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head +
                                (long long)(s.tok_off + pivot_tok) * sh.ks_tok;
-    const float den = (float)(1 + e4.w);
+    float den = (float)(1 + e4.w);
+    if constexpr (WEIGHTED) {
+      den = 1.f;  // the pivot's own weight, then the partial sums in task order
+      for (int pi = 0; pi < e4.z; ++pi) den += c.partial_w[unit * sh.part_total + e4.y + pi];
+    }
     // lanes [0, NCH) fold K chunks, lanes [NCH, 2 NCH) fold V chunks
     for (int idx = lane; idx < 2 * NCH; idx += 64) {
       const int tensor = idx / NCH, ch = idx % NCH;
@@ -301,8 +343,8 @@ __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
   }
 }
 
-template <bool BF16, int D>
-hipError_t launch_merge_t(const Ctx &c, int nw_shift, size_t lds) {
+template <bool BF16, int D, bool WEIGHTED>
+hipError_t launch_merge_w(const Ctx &c, int nw_shift, size_t lds) {
   const Shape &sh = c.sh;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_csr_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -313,13 +355,18 @@ hipError_t launch_merge_t(const Ctx &c, int nw_shift, size_t lds) {
   }
   {
     ProfScope ps(c.stream, KID_MERGE_TASKS);
-    merge_tasks_kernel<BF16, D><<<dim3((sh.tasks_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+    merge_tasks_kernel<BF16, D, WEIGHTED><<<dim3((sh.tasks_total + 3) / 4, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
   }
   {
     ProfScope ps(c.stream, KID_MERGE_FOLD);
-    merge_fold_kernel<BF16, D><<<dim3(sh.batch * kFoldGroups, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
+    merge_fold_kernel<BF16, D, WEIGHTED><<<dim3(sh.batch * kFoldGroups, sh.Hkv, sh.n_layers), 256, 0, c.stream>>>(c);
   }
   return hipGetLastError();
+}
+
+template <bool BF16, int D>
+hipError_t launch_merge_t(const Ctx &c, int nw_shift, size_t lds) {
+  return c.sh.weighted_merge ? launch_merge_w<BF16, D, true>(c, nw_shift, lds) : launch_merge_w<BF16, D, false>(c, nw_shift, lds);
 }
 
 }  // namespace

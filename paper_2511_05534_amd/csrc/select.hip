@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
       sh_rho = rho;
       if (gkv == 0) {
         c.rho[l * sh.batch + b] = rho;
-        c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
+        c.mode[l * sh.batch + b] = (rho > sh.theta) != (sh.invert_flow != 0) ? 1 : 0;
       }
       c.n_dropped[unit * sh.batch + b] = 0;
     }
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
   int *assign = c.assign + unit * sh.T + s.tok_off;
   select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
   __syncthreads();  // kept[] is read back below; sh_rho is set
-  const bool cross = sh_rho > sh.theta;
+  const bool cross = (sh_rho > sh.theta) != (sh.invert_flow != 0);
 
   // ---- lists of eligible pivots per token class --------------------------------------------------
   const int Bp = (s.B + 31) & ~31;

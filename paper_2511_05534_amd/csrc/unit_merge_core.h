@@ -20,7 +20,7 @@ constexpr int kF3Chunks = 4;   // 64-token chunks a wave walks: ceil(1024 / 4 wa
 constexpr int kUnitChunk = 64;  // members per task of a slot that is cut up (keeps the partial sums in LDS few)
 
 struct MergeLds {  // element offsets (ints) into the dynamic LDS block
-  int tbl, kept, copies, members, tasks, multi, partials, total_bytes;
+  int tbl, kept, copies, members, tasks, multi, partials, partial_w, total_bytes;
 };
 
 __host__ __device__ inline MergeLds merge_lds_layout(int maxB, int maxE, int d) {
@@ -34,6 +34,7 @@ __host__ __device__ inline MergeLds merge_lds_layout(int maxB, int maxE, int d) 
   m.tasks = off; off += 4 * (maxB + maxE / kUnitChunk + 1);
   m.multi = off; off += 4 * (maxE / (kUnitChunk + 1) + 1);
   m.partials = off; off += (2 * (maxE / kUnitChunk) + 2) * 2 * d;
+  m.partial_w = off; off += 2 * (maxE / kUnitChunk) + 2;  // weight sums of the partials (weighted merge)
   m.total_bytes = off * 4;
   return m;
 }
@@ -56,7 +57,10 @@ __device__ __forceinline__ unsigned long long same_slot_lanes(bool member, int s
 // slots become tasks (a slot, or a chunk of at most kUnitChunk members of a larger slot) that a
 // group adds up row after row, U row loads in flight, large chunks first; slots cut into several
 // tasks are folded from their partial sums at the end.
-template <int D, int U = 8>
+// WEIGHTED: the similarity-weighted mean instead of the uniform one: the pivot counts 1, a member
+// max(u, 0) with u the cosine of its key to the pivot's key (0 for a zero row), computed here from
+// the rows that are being merged; V rows take the weights of their K rows.
+template <int D, int U = 8, bool WEIGHTED = false>
 __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, long long unit, int l, int gkv,
                                                 const int *assign, const int *kept_src, int *lds_i, int maxB,
                                                 int maxE, long long *lds_wave, int *sh_next_p) {
@@ -71,6 +75,7 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   int4 *tasks = reinterpret_cast<int4 *>(lds_i + lay.tasks);  // (slot, first member, members, partial or -1)
   int4 *multi = reinterpret_cast<int4 *>(lds_i + lay.multi);  // (slot, first partial, partials, members)
   float *partials = reinterpret_cast<float *>(lds_i + lay.partials);
+  float *partial_w = reinterpret_cast<float *>(lds_i + lay.partial_w);
   int &sh_next = *sh_next_p;           // next task nobody has taken yet
 
   const Shape &sh = c.sh;
@@ -196,6 +201,7 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   int4 task = have ? tasks[q] : make_int4(0, 0, 0, 0);
   int j0 = 0;
   float ak[EPC], av[EPC];
+  float wsum = 0.f;  // weighted merge: sum of the weights added so far
 #pragma unroll
   for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
   while (__any(have)) {
@@ -216,24 +222,58 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
         const int tok = mem[max(j, lead)];
         tokv[u] = j < lead ? pivot_tok : tok;
       }
+      uint4 pkc;
+      if constexpr (WEIGHTED) pkc = K[(long long)pivot_tok * sh.ks_tok + ch];  // the cosines need the pivot's key
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         kc[u] = K[(long long)tokv[u] * sh.ks_tok + ch];
         vc[u] = V[(long long)tokv[u] * sh.ks_tok + ch];
       }
+      if constexpr (WEIGHTED) {
+        float pk[EPC], fk[U][EPC], dot[U], ss[U];
+        chunk_to_floats<kBF16>(pkc, pk);
+        float pss = 0.f;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float fk[EPC], fv[EPC];
-        chunk_to_floats<kBF16>(kc[u], fk);
-        chunk_to_floats<kBF16>(vc[u], fv);
-        const bool real = j0 + u < nrows;
+        for (int e = 0; e < EPC; ++e) pss = fmaf(pk[e], pk[e], pss);
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) { ak[e] += real ? fk[e] : 0.f; av[e] += real ? fv[e] : 0.f; }
+        for (int u = 0; u < U; ++u) {
+          chunk_to_floats<kBF16>(kc[u], fk[u]);
+          dot[u] = ss[u] = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { dot[u] = fmaf(fk[u][e], pk[e], dot[u]); ss[u] = fmaf(fk[u][e], fk[u][e], ss[u]); }
+        }
+#pragma unroll
+        for (int o = LPR / 2; o >= 1; o >>= 1) {  // over the lanes that share the row
+          pss += __shfl_xor(pss, o, 64);
+#pragma unroll
+          for (int u = 0; u < U; ++u) { dot[u] += __shfl_xor(dot[u], o, 64); ss[u] += __shfl_xor(ss[u], o, 64); }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float fv[EPC];
+          chunk_to_floats<kBF16>(vc[u], fv);
+          const int j = j0 + u;
+          float w = ss[u] > 0.f && pss > 0.f ? fmaxf(dot[u] / (sqrtf(ss[u]) * sqrtf(pss)), 0.f) : 0.f;
+          w = j < lead ? 1.f : (j < nrows ? w : 0.f);
+          wsum += w;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { ak[e] = fmaf(w, fk[u][e], ak[e]); av[e] = fmaf(w, fv[e], av[e]); }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float fk[EPC], fv[EPC];
+          chunk_to_floats<kBF16>(kc[u], fk);
+          chunk_to_floats<kBF16>(vc[u], fv);
+          const bool real = j0 + u < nrows;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { ak[e] += real ? fk[e] : 0.f; av[e] += real ? fv[e] : 0.f; }
+        }
       }
       j0 += U;
       if (j0 >= nrows) {  // task finished: write its result, move to the next one of this group
         if (lead) {
-          const float w = 1.0f / (float)(1 + task.z);  // uniform merge weight
+          const float w = WEIGHTED ? 1.0f / wsum : 1.0f / (float)(1 + task.z);  // uniform merge weight 1/(1+n)
 #pragma unroll
           for (int e = 0; e < EPC; ++e) { ak[e] *= w; av[e] *= w; }
           Ko[(long long)task.x * LPR + ch] = floats_to_chunk<kBF16>(ak);
@@ -242,6 +282,7 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
           float *pp = partials + (long long)task.w * 2 * D + ch * EPC;
 #pragma unroll
           for (int e = 0; e < EPC; ++e) { pp[e] = ak[e]; pp[D + e] = av[e]; }
+          if (WEIGHTED && ch == 0) partial_w[task.w] = wsum;
         }
         int nq = 0;
         if (ch == 0) nq = atomicAdd(&sh_next, 1);
@@ -249,6 +290,7 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
         have = q < n_tasks;
         if (have) task = tasks[q];
         j0 = 0;
+        wsum = 0.f;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
       }
@@ -261,7 +303,12 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   for (int qm = wave; qm < n_multi; qm += kF3Waves) {
     const int4 e4 = multi[qm];
     const int pivot_tok = lds_kept[e4.x];
-    const float w = 1.0f / (float)(1 + e4.w);
+    float w = 1.0f / (float)(1 + e4.w);
+    if constexpr (WEIGHTED) {
+      float tot = 1.f;  // the pivot's own weight, then the partial sums in task order
+      for (int pi = 0; pi < e4.z; ++pi) tot += partial_w[e4.y + pi];
+      w = 1.0f / tot;
+    }
     if (lane < 2 * LPR) {
       const int tensor = lane / LPR, cch = lane % LPR;
       const uint4 *src = tensor ? V : K;

@@ -444,11 +444,11 @@ __device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, ch
     sh_rho = rho;
     if (gkv == 0) {
       c.rho[l * sh.batch + b] = rho;
-      c.mode[l * sh.batch + b] = rho > sh.theta ? 1 : 0;
+      c.mode[l * sh.batch + b] = (rho > sh.theta) != (sh.invert_flow != 0) ? 1 : 0;
     }
   }
   __syncthreads();
-  const bool mode_cross = sh_rho > sh.theta;
+  const bool mode_cross = (sh_rho > sh.theta) != (sh.invert_flow != 0);
   if (mode_cross) return;  // unit_plan_kernel has matched this unit as a cross-modal layer does
 
   // intra-modal layer: the split again (same result) and the match restricted to the token's modality
@@ -555,7 +555,7 @@ __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad
 // Merge of one unit per workgroup (unit_merge_core.h).  U rows in flight per lane group.
 // FLOW: the workgroup first settles its layer's strategy and, in an intra-modal layer, matches its
 // unit again (what unit_match_kernel does), so that plan and merge take two launches, not three.
-template <int D, int U, bool FLOW>
+template <int D, int U, bool FLOW, bool WEIGHTED>
 __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB, int maxE, int b_pad) {
   extern __shared__ __align__(16) int lds_i[];
   __shared__ long long lds_wave[kF3Waves + 1];
@@ -569,7 +569,7 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
   }
   const SeqInfo s = inline_seq(c.inl, b);
   const long long unit = (long long)l * sh.Hkv + gkv;
-  unit_merge_body<D, U>(c, s, unit, l, gkv, c.assign + unit * sh.T + s.tok_off, c.kept_idx + unit * sh.SB + s.kept_off,
+  unit_merge_body<D, U, WEIGHTED>(c, s, unit, l, gkv, c.assign + unit * sh.T + s.tok_off, c.kept_idx + unit * sh.SB + s.kept_off,
                         lds_i, maxB, maxE, lds_wave, &sh_next);
 }
 
@@ -619,18 +619,24 @@ hipError_t launch_f2(const Ctx &c) {
   return hipGetLastError();
 }
 
-template <int D, int U, bool FLOW>
-hipError_t launch_f3(const Ctx &c) {
+template <int D, int U, bool FLOW, bool WEIGHTED>
+hipError_t launch_f3w(const Ctx &c) {
   const int b_pad = (c.sh.maxB + 31) / 32 * 32;
   size_t lds = (size_t)merge_lds_layout(c.sh.maxB, c.sh.maxE, D).total_bytes;
   if (FLOW && match_lds_bytes(c.sh, b_pad) > lds) lds = match_lds_bytes(c.sh, b_pad);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_merge_kernel<D, U, FLOW>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_merge_kernel<D, U, FLOW, WEIGHTED>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, FLOW ? KID_UNIT_FLOW_MERGE : KID_UNIT_MERGE);
-  unit_merge_kernel<D, U, FLOW><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kF3Threads, lds, c.stream>>>(
+  unit_merge_kernel<D, U, FLOW, WEIGHTED><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kF3Threads, lds, c.stream>>>(
       c, c.sh.maxB, c.sh.maxE, b_pad);
   return hipGetLastError();
+}
+
+template <int D, int U, bool FLOW>
+hipError_t launch_f3(const Ctx &c) {
+  // the weighted variant keeps U = 4 rows in flight: its cosines need every row of a trip in registers
+  return c.sh.weighted_merge ? launch_f3w<D, (U > 4 ? 4 : U), FLOW, true>(c) : launch_f3w<D, U, FLOW, false>(c);
 }
 
 }  // namespace

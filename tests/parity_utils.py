@@ -64,8 +64,10 @@ class Report:
 
 
 def check_layer(oracle, wl, gpu, layer, theta=None, tau=None, kv_heads=None, seqs=None, report=None,
-                tensors_np=None):
-    """Compare one layer of the GPU result with the oracle (all sequences, chosen kv heads)."""
+                tensors_np=None, flags=0):
+    """Compare one layer of the GPU result with the oracle (all sequences, chosen kv heads).
+    flags: the FLOWMM_FLAG_* bits of the run (inverted flow rule, similarity-weighted merge)."""
+    invert, weighted = bool(flags & 2), bool(flags & 4)
     rep = report or Report()
     theta = wl.theta if theta is None else theta
     tau = wl.tau if tau is None else tau
@@ -79,7 +81,7 @@ def check_layer(oracle, wl, gpu, layer, theta=None, tau=None, kv_heads=None, seq
         Kb, Vb = K[:, sl, :], V[:, sl, :]
         Qb = Q[:, b * W:(b + 1) * W, :]
         I_o, cross_o = oracle.score(Kb, Qb, mod)
-        rho_o, mode_o = oracle.flow(cross_o, theta)
+        rho_o, mode_o = oracle.flow(cross_o, theta, invert)
         # (1) importance and rho by relative tolerance
         I_g = gpu["importance"][layer][:, sl].astype(np.float64)
         rel = np.abs(I_g - I_o) / np.maximum(I_o, 1e-30)
@@ -145,7 +147,10 @@ def check_layer(oracle, wl, gpu, layer, theta=None, tau=None, kv_heads=None, seq
                     assert u >= ub[i] - MARGIN * abs(ub[i]) - 1e-12
                 rep.match_inband += len(differ)
             # (4) merge, teacher-forced from the GPU's assignment
-            ko, vo, _ = oracle.merge(Kb[g], Vb[g], kept_g, assign_g)
+            if weighted:
+                ko, vo, _, _ = oracle.merge_weighted(Kb[g], Vb[g], kept_g, assign_g)
+            else:
+                ko, vo, _ = oracle.merge(Kb[g], Vb[g], kept_g, assign_g)
             rows = slice(int(cuk[b]), int(cuk[b + 1]))
             for name, o in (("K_out", ko), ("V_out", vo)):
                 got = gpu[name][layer][g][rows].astype(np.float64)

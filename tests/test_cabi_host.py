@@ -67,7 +67,7 @@ BAD = [
     (dict(k_strides=(2 * 500 * 128, 500 * 128, 132)), fb.FLOWMM_EINVAL, "16 bytes"),
     (dict(n_q_heads=64, n_kv_heads=1, window=128, budgets=[130, 140]), fb.FLOWMM_EUNSUPPORTED, "LDS"),
     (dict(seqlens=[300, 0], budgets=[30, 0]), fb.FLOWMM_EINVAL, "increasing"),
-    (dict(flags=2), fb.FLOWMM_EINVAL, "flags"),
+    (dict(flags=8), fb.FLOWMM_EINVAL, "flags"),
 ]
 
 

@@ -72,6 +72,52 @@ def test_both_paths_agree_on_decisions():
     assert (a["mode"] == b["mode"]).all()
 
 
+VARIANT_SHAPES = {
+    "unit": dict(Hq=4, Hkv=2, spans=((40, 300, 60),)),
+    "unit_big_slots": dict(Hq=2, Hkv=2, W=32, spans=((60, 880, 60),), pct=(8,)),
+    "unit_d64": dict(Hq=2, Hkv=2, d=64, W=24, spans=((50, 500, 77),)),
+    "f32": dict(dtype="f32", Hq=4, Hkv=4, d=64, W=16, spans=((32, 256, 32),), pct=(20,)),
+    "f32_d128": dict(dtype="f32", Hq=2, Hkv=1, d=128, W=8, spans=((20, 200, 19),)),
+    "multi_tile": dict(Hq=4, Hkv=1, W=32, spans=((100, 500, 50, 600, 50),), pct=(7,)),
+    "batch_of_3": dict(Hq=4, Hkv=2, W=16, spans=((30, 260, 40), (64, 700, 69), (20, 100, 17)), pct=(10, 20, 5)),
+}
+
+
+@pytest.mark.parametrize("path", ["auto", "generic", "fused"])
+@pytest.mark.parametrize("variant", ["inverted_flow", "weighted_merge", "both"])
+@pytest.mark.parametrize("name", list(VARIANT_SHAPES))
+def test_ablation_variants_match_oracle(oracle, name, variant, path):
+    """The switches of the paper's component ablation: the strategy misaligned with the flow
+    (FLOWMM_FLAG_INVERT_FLOW) and the similarity-weighted merge (FLOWMM_FLAG_WEIGHTED_MERGE)."""
+    flags = {"inverted_flow": 2, "weighted_merge": 4, "both": 6}[variant]
+    for theta in ((0.25, 2.0) if flags & 2 else (0.25,)):  # the inverse of both outcomes of the rule
+        w = small(name, theta=theta, **VARIANT_SHAPES[name])
+        print(f"case {name} [{variant}, {path}] theta={theta}: L={w.seqlens} B={w.budgets} dtype={w.dtype}", flush=True)
+        gpu = run_gpu(w, flags=flags | (1 if path == "generic" else 0), fused=path == "fused")
+        if flags & 2:
+            assert (gpu["mode"] == (0 if gpu["rho"].min() > theta else 1)).all()
+        rep = Report()
+        for l in range(w.n_layers):
+            check_layer(oracle, w, gpu, l, report=rep, flags=flags)
+        print(rep, flush=True)
+
+
+def test_weighted_merge_of_identical_keys_is_the_uniform_mean():
+    """Every weight is 1 when all keys point the same way: both merge operators must agree."""
+    import torch
+    w = small("same_direction", Hq=2, Hkv=2, spans=((40, 300, 60),), n_layers=1)
+    K, V, Q = upload(w)
+    direction = torch.randn(w.head_dim, device=K.device).to(K.dtype)
+    scale = (1 + torch.arange(K.shape[2], device=K.device) % 4).to(K.dtype)[None, None, :, None]  # exact multiples
+    K = (direction[None, None, None, :] * scale).expand_as(K).contiguous()
+    for flags in (0, 1):
+        a = run_gpu(w, tensors=(K, V, Q), flags=flags)
+        b = run_gpu(w, tensors=(K, V, Q), flags=flags | 4)
+        assert (a["assign"] == b["assign"]).all()
+        assert np.allclose(a["V_out"], b["V_out"], rtol=0, atol=2e-2)
+        assert np.allclose(a["K_out"], b["K_out"], rtol=0, atol=2e-2 * 4)
+
+
 def test_one_call_equals_two_calls():
     """flowmm_plan_merge against flowmm_plan + flowmm_merge: the same decisions up to the last bits of
     the importances (the two spread the key tiles over their waves differently), and bit-identical
