@@ -132,6 +132,22 @@ flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K, const voi
                                 const flowmm_plan_buffers *plan, void *K_out, void *V_out, void *workspace,
                                 size_t workspace_bytes, void *stream);
 
+/* The cross-modal interaction ratio with EVERY token of the prompt as a query: the rho^l equation
+ * of the paper (Information Flow Guided Merging) evaluated literally over the causal prefill
+ * attention, instead of the estimate from the last `window` queries that flowmm_plan uses.
+ *   rho[l][b] = (1/Hq) sum_h (1/L_b) sum_r  (mass query r sends to keys of the other modality)
+ *                                           / (total mass of query r),
+ *   mode[l][b] = FLOWMM_MODE_CROSS iff rho > theta (inverted under FLOWMM_FLAG_INVERT_FLOW).
+ * Q_full [Lyr][Hq][T][d]: the query of every packed token, dtype of K, read through the three
+ * strides given here (elements; head_dim contiguous).  K, p, workspace (size from
+ * flowmm_plan_sizes), stream and the rules for errors as in flowmm_plan; window, budgets and tau
+ * are validated but not used.  rho, mode: device, [Lyr][batch].  Cost grows with L^2: this is a
+ * measurement, and a way to supply the strategy when the prefill can provide all queries. */
+flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K, const void *Q_full,
+                                int64_t qf_stride_layer, int64_t qf_stride_head, int64_t qf_stride_token,
+                                float *rho, int32_t *mode, void *workspace, size_t workspace_bytes,
+                                void *stream);
+
 /* Message of the last failing call on this thread (static storage, never NULL). */
 const char *flowmm_last_error(void);
 

@@ -19,7 +19,8 @@ FLOWMM_F32, FLOWMM_BF16 = 0, 1
 FLOWMM_FLAG_GENERIC_PATH, FLOWMM_FLAG_INVERT_FLOW, FLOWMM_FLAG_WEIGHTED_MERGE = 1, 2, 4
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
-EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_last_error",
+EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_flow_exact",
+           "flowmm_last_error",
            "flowmm_profile_kernel_count", "flowmm_profile_kernel_name", "flowmm_profile_select",
            "flowmm_profile_collect")
 
@@ -75,6 +76,9 @@ def load(build_if_missing: bool = True):
         lib.flowmm_plan_merge.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+        lib.flowmm_flow_exact.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                          C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.flowmm_flow_exact.restype = C.c_int
         for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge, lib.flowmm_plan_merge, lib.flowmm_profile_collect,
                   lib.flowmm_profile_kernel_count):
             f.restype = C.c_int
@@ -169,6 +173,13 @@ def flowmm_plan_merge(params: Params, K: int, V: int, Q_window: int, plan_ptrs: 
                                     C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
+def flowmm_flow_exact(params: Params, K: int, Q_full: int, q_strides: Tuple[int, int, int], rho: int, mode: int,
+                      workspace: int, workspace_bytes: int, stream: int = 0):
+    _check(load().flowmm_flow_exact(C.byref(params.c), C.c_void_p(K), C.c_void_p(Q_full), *[C.c_int64(int(x)) for x in q_strides],
+                                    C.c_void_p(rho), C.c_void_p(mode), C.c_void_p(workspace),
+                                    C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+
 def flowmm_profile_select(names: str = ""):
     load().flowmm_profile_select(names.encode())
 
@@ -233,6 +244,12 @@ class DeviceBuffers:
         flowmm_plan_merge(self.params, K.data_ptr(), V.data_ptr(), Q.data_ptr(), self.plan_ptrs,
                           self.K_out.data_ptr(), self.V_out.data_ptr(), self.workspace.data_ptr(),
                           self.workspace_bytes, stream)
+
+    def flow_exact(self, K, Q_full, stream: int = 0):
+        """Q_full [Lyr][Hq][T][d] contiguous; fills self.rho and self.mode."""
+        Hq, T, d = Q_full.shape[1:]
+        flowmm_flow_exact(self.params, K.data_ptr(), Q_full.data_ptr(), (Hq * T * d, T * d, d), self.rho.data_ptr(),
+                          self.mode.data_ptr(), self.workspace.data_ptr(), self.workspace_bytes, stream)
 
     def merge(self, K, V, stream: int = 0):
         flowmm_merge(self.params, self.plan_ptrs, K.data_ptr(), V.data_ptr(), self.K_out.data_ptr(),

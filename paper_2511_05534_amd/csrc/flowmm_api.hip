@@ -85,7 +85,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   const int batch = p->batch;
   const int match_tile = match_tile_tokens(sh.bf16), score_tile = score_tile_keys(sh.bf16);
   std::vector<int32_t> cu_score(batch + 1, 0), cu_match(batch + 1, 0), cu_task(batch + 1, 0),
-      cu_multi(batch + 1, 0), cu_part(batch + 1, 0), cu_bp(batch + 1, 0);
+      cu_multi(batch + 1, 0), cu_part(batch + 1, 0), cu_bp(batch + 1, 0), cu_flowq(batch + 1, 0);
   std::vector<int32_t> seq((size_t)batch * SW_WORDS, 0);
   int64_t sumB = 0;
   int maxB = 0, maxL = 0, maxE = 0;
@@ -116,6 +116,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     // an intra-modal layer matches text and image tokens in separate tiles: one tile more at most
     cu_match[b + 1] = cu_match[b] + (L + match_tile - 1) / match_tile + 1;
     cu_bp[b + 1] = cu_bp[b] + (B + 31) / 32 * 32;
+    cu_flowq[b + 1] = cu_flowq[b] + (L + kFlowQueryTile - 1) / kFlowQueryTile;
     cu_task[b + 1] = cu_task[b] + B + E / kTaskChunk + 1;
     cu_multi[b + 1] = cu_multi[b] + E / (kTaskChunk + 1) + 1;
     cu_part[b + 1] = cu_part[b] + 2 * (E / kTaskChunk) + 2;
@@ -154,6 +155,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   sh.tiles_score = cu_score[batch]; sh.tiles_match = cu_match[batch];
   sh.tasks_total = cu_task[batch]; sh.multi_total = cu_multi[batch]; sh.part_total = cu_part[batch];
   sh.SBP = cu_bp[batch];
+  sh.flowq_total = cu_flowq[batch];
   if (score_lds_bytes(sh) > kLdsLimit)
     return fail(FLOWMM_EUNSUPPORTED, "(n_q_heads/n_kv_heads) x window = %d query rows per kv head do not fit in LDS", sh.R_pad);
   if (merge_csr_lds_bytes(maxB) > kLdsLimit)
@@ -178,6 +180,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   w[MW_OFF_CU_MULTI] = append(cu_multi);
   w[MW_OFF_CU_PART] = append(cu_part);
   w[MW_OFF_CU_BP] = append(cu_bp);
+  w[MW_OFF_CU_FLOWQ] = append(cu_flowq);
 
   // plan buffers
   lo.plan_bytes[0] = (size_t)units * T * 4;
@@ -197,6 +200,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   rg.part_stats = off; off += align256((size_t)units * sh.tiles_score * sh.R_pad * sizeof(float2));
   rg.rowstat = off; off += align256((size_t)units * batch * sh.R_pad * sizeof(float2));
   rg.cross_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.tiles_score * 4);
+  rg.flow_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.flowq_total * 4);
   if (!sh.unit_path) {
     rg.pl_slot = off; off += align256((size_t)units * 2 * sh.SBP * 4);
     rg.pl_tok = off; off += align256((size_t)units * 2 * sh.SBP * 4);
@@ -397,6 +401,42 @@ FLOWMM_API flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K
   if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
   if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
   if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K, const void *Q_full,
+                                int64_t qf_stride_layer, int64_t qf_stride_head, int64_t qf_stride_token,
+                                float *rho, int32_t *mode, void *workspace, size_t workspace_bytes, void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (!K || !Q_full || !rho || !mode || !workspace) return fail(FLOWMM_EINVAL, "K, Q_full, rho, mode and workspace must not be NULL");
+  if (misaligned(K) || misaligned(Q_full) || misaligned(workspace))
+    return fail(FLOWMM_EINVAL, "K, Q_full and workspace must be 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(rho) | reinterpret_cast<uintptr_t>(mode)) & 3)
+    return fail(FLOWMM_EINVAL, "rho and mode must be 4-byte aligned");
+  const int epc = lo.sh.bf16 ? 8 : 4;
+  const int64_t strides[3] = {qf_stride_layer, qf_stride_head, qf_stride_token};
+  for (int i = 0; i < 3; ++i)
+    if (strides[i] < 0 || strides[i] % epc != 0)
+      return fail(FLOWMM_EINVAL, "strides must be non-negative multiples of 16 bytes (%d elements)", epc);
+  if (qf_stride_token < lo.sh.d) return fail(FLOWMM_EINVAL, "token strides must be at least head_dim");
+  if (workspace_bytes < lo.workspace_bytes)
+    return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
+  flowmm_plan_buffers none;
+  std::memset(&none, 0, sizeof(none));
+  Ctx c;
+  fill_ctx(c, lo, &none, workspace, stream);
+  c.K = K;
+  FlowExactArgs a;
+  a.Q = Q_full;
+  a.qs_layer = qf_stride_layer / epc; a.qs_head = qf_stride_head / epc; a.qs_tok = qf_stride_token / epc;
+  a.part = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + lo.rg.flow_part);
+  a.qtiles_total = lo.sh.flowq_total;
+  a.rho = rho; a.mode = mode;
+  hipError_t e;
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_flow_exact(c, a)) != hipSuccess) return hip_fail(e, "exact flow-ratio kernels");
   return FLOWMM_OK;
 }
 

@@ -42,6 +42,17 @@ struct Ctx {
   float *partial_w;    // [Lyr][Hkv][part_total]          weight sums of those partials (weighted merge)
 };
 
+// arguments of the exact (all-query) flow ratio that are not part of a plan
+struct FlowExactArgs {
+  const void *Q;                          // [Lyr][Hq][T][d] queries of every prompt token
+  long long qs_layer, qs_head, qs_tok;    // strides in 16-byte chunks
+  float *part;                            // [Lyr][Hq][qtiles_total] sum of the rows' cross-modal shares per query tile
+  int qtiles_total;
+  float *rho;                             // [Lyr][batch]
+  int *mode;                              // [Lyr][batch]
+};
+hipError_t launch_flow_exact(const Ctx &c, const FlowExactArgs &a);
+
 constexpr int kMetaChunkWords = 960;
 struct MetaChunk { int w[kMetaChunkWords]; };
 

@@ -21,7 +21,8 @@ enum MetaWord {
   MW_OFF_CU_PART,  // word offset of cu_part[batch+1]    (upper bounds)
   MW_OFF_CU_BP,    // word offset of cu_bp[batch+1]      (budgets rounded up to 32, prefix sums)
   MW_ZERO16,       // four zero words (a 16-byte aligned chunk of zeros for padding loads)
-  MW_HEADER = 16
+  MW_OFF_CU_FLOWQ = 16,  // word offset of cu_flowq[batch+1] (query tiles of the exact flow ratio)
+  MW_HEADER = 20
 };
 
 // per-sequence record
@@ -49,6 +50,7 @@ constexpr int match_subs(bool bf16) { return bf16 ? 4 : 2; }
 constexpr int match_tile_tokens(bool bf16) { return kMatchWaves * 32 * match_subs(bf16); }  // tokens per workgroup
 // packed pivot rows staged in LDS at a time: 32 KB worth, 128 rows at most (nch = 16-byte chunks per row)
 constexpr int match_tile_rows(int nch) { return 2048 / nch < 128 ? 2048 / nch : 128; }
+constexpr int kFlowQueryTile = 256;                          // query rows per workgroup of the exact flow ratio
 constexpr int kTaskChunk = 32;                               // members summed by one wave task
 constexpr int kCsrWaves = 16;                                // waves of the CSR-building workgroup
 constexpr int kFoldGroups = 4;                               // workgroups per (sequence, kv head, layer) that fold split slots
@@ -60,7 +62,7 @@ struct Shape {
   int invert_flow;     // 1: the misaligned strategy (cross-modal merging iff NOT rho > theta)
   int weighted_merge;  // 1: similarity-weighted mean instead of the uniform one
   int SBP;        // sum over sequences of the budget rounded up to a multiple of 32
-  int tiles_score, tiles_match, tasks_total, multi_total, part_total;
+  int tiles_score, tiles_match, tasks_total, multi_total, part_total, flowq_total;
   float scale_log2e, theta;
   long long ks_layer, ks_head, ks_tok;  // K/V strides in 16-byte chunks
   long long qs_layer, qs_head, qs_tok;  // Q strides in 16-byte chunks
@@ -83,6 +85,7 @@ struct InlineMeta {
 struct Regions {
   size_t meta, mod, cls_order;                              // both calls
   size_t part_stats, rowstat, cross_part;                   // plan: score
+  size_t flow_part;                                         // exact flow ratio: [Lyr][Hq][flowq_total]
   size_t pl_slot, pl_tok, pl_w, pl_n, pack;                 // plan: match
   size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials, partial_w;  // merge
   size_t plan_end, merge_end;

@@ -147,6 +147,17 @@ class Workload:
         out.append(self._round(q))
         return tuple(out)
 
+    def layer_queries_full(self, layer: int):
+        """Queries of EVERY prompt token, Q_full [Hq][T][d] (for the exact flow ratio): text rows N(0,1),
+        image rows shifted and scaled like the image keys; float32 array of dtype-rounded values."""
+        T, d = self.total_tokens, self.head_dim
+        mu, sc, _ = self._token_affine()
+        rng = np.random.default_rng([self.seed, layer, 3])
+        q = rng.standard_normal((self.n_q_heads, T, d), dtype=np.float32)
+        q *= sc[None, :, None]
+        q += mu[None, :, None]
+        return self._round(q)
+
     def all_tensors(self):
         """K, V [Lyr][Hkv][T][d] and Q [Lyr][Hq][batch*W][d] stacked over layers."""
         Ks, Vs, Qs = [], [], []

@@ -118,6 +118,52 @@ def test_weighted_merge_of_identical_keys_is_the_uniform_mean():
         assert np.allclose(a["K_out"], b["K_out"], rtol=0, atol=2e-2 * 4)
 
 
+FLOW_EXACT_CASES = {
+    "mha_one_tile": dict(Hq=2, Hkv=2, spans=((40, 150, 30),)),
+    "gqa_three_tiles_ragged": dict(Hq=4, Hkv=2, spans=((37, 411, 83, 120),)),
+    "d64": dict(Hq=2, Hkv=2, d=64, W=24, spans=((50, 500, 77),)),
+    "f32_d64": dict(dtype="f32", Hq=4, Hkv=4, d=64, W=16, spans=((32, 256, 32),)),
+    "f32_d128": dict(dtype="f32", Hq=2, Hkv=1, d=128, W=8, spans=((20, 200, 19, 300),)),
+    "image_first": dict(Hq=2, Hkv=2, W=16, spans=((200, 100),), first_mod=wl.IMAGE),
+    "text_only": dict(Hq=2, Hkv=1, W=16, spans=((300,),)),
+    "many_key_steps": dict(Hq=2, Hkv=1, W=32, spans=((100, 500, 50, 600, 50),)),
+    "batch_of_3": dict(Hq=4, Hkv=2, W=16, spans=((30, 260, 40), (64, 700, 69), (20, 100, 17)), pct=(10, 20, 5)),
+    "shortest": dict(Hq=1, Hkv=1, W=1, spans=((1,),), budgets=(1,), n_layers=1),
+}
+
+
+@pytest.mark.parametrize("name", list(FLOW_EXACT_CASES))
+def test_flow_exact_matches_the_literal_ratio(oracle, name):
+    """flowmm_flow_exact against the oracle's score with every token as a proxy (W = L), which a CPU
+    pin shows to be the paper's rho equation evaluated on the dense L x L attention matrix."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    w = small(name, **FLOW_EXACT_CASES[name])
+    print(f"case {name}: L={w.seqlens} dtype={w.dtype}", flush=True)
+    K, V, Q = upload(w)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    qf_np = [w.layer_queries_full(l) for l in range(w.n_layers)]
+    Qf = torch.stack([torch.from_numpy(q) for q in qf_np]).to("cuda:0").to(tdt)
+    for theta, flags in ((w.theta, 0), (0.05, 2)):
+        params = fb.Params.from_workload(w, theta=theta, flags=flags)
+        bufs = fb.DeviceBuffers(params)
+        bufs.rho.fill_(-1.0)
+        bufs.mode.fill_(-1)
+        bufs.flow_exact(K, Qf, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        rho_g, mode_g = bufs.rho.cpu().numpy(), bufs.mode.cpu().numpy()
+        cu = w.cu_seqlens
+        for l in range(w.n_layers):
+            Kl = w.layer_tensors(l)[0]
+            for b in range(w.batch):
+                sl = slice(int(cu[b]), int(cu[b + 1]))
+                _, cross = oracle.score(Kl[:, sl], qf_np[l][:, sl], w.modality(b))  # W = L: every token is a query
+                rho_o, mode_o = oracle.flow(cross, theta, invert=bool(flags & 2))
+                assert abs(rho_g[l, b] - rho_o) <= 2e-4 * max(rho_o, 1e-6) + 1e-7, (l, b, rho_g[l, b], rho_o)
+                if abs(rho_o - theta) > 1e-3 * abs(theta):
+                    assert mode_g[l, b] == mode_o
+
+
 def test_one_call_equals_two_calls():
     """flowmm_plan_merge against flowmm_plan + flowmm_merge: the same decisions up to the last bits of
     the importances (the two spread the key tiles over their waves differently), and bit-identical
