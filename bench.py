@@ -91,6 +91,46 @@ def cpu_baseline(wl, budget_s: float):
                       f"scaled linearly to the full depth"}
 
 
+def bench_flow_exact(args, wl, dev):
+    """The exact flow ratio is a dense causal contraction: report it against the MFMA peak of its dtype."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    K, V, Q = fb.upload_workload(wl, dev)
+    del V, Q
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    Qf = torch.randn((wl.n_layers, wl.n_q_heads, wl.total_tokens, wl.head_dim), generator=gen, device=dev).to(tdt)
+    params = fb.Params.from_workload(wl)
+    bufs = fb.DeviceBuffers(params, dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(args.warmup):
+        bufs.flow_exact(K, Qf, stream)
+    torch.cuda.synchronize()
+    fb.flowmm_profile_select("flow_exact")
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        bufs.flow_exact(K, Qf, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms, n = fb.flowmm_profile_collect()["flow_exact"]
+    fb.flowmm_profile_select("")
+    flops = sum(2.0 * wl.head_dim * L * (L + 1) / 2 for L in wl.seqlens) * wl.n_q_heads * wl.n_layers
+    peak = 2500.0 if wl.dtype == "bf16" else 157.3
+    k_us = 1e3 * ms / n
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    print(json.dumps({
+        "metric": "exact cross-modal interaction ratio (all prompt queries), prompt tokens per second",
+        "value": wl.total_tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {wl.name}", "layers": wl.n_layers, "q_heads": wl.n_q_heads,
+                   "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "seqlens": wl.seqlens, "entry_point": "flowmm_flow_exact"},
+        "roofline": {"bound": "mfma", "kernel": "flow_exact", "achieved": flops / (k_us * 1e-6) / 1e12, "peak": peak,
+                     "unit": "TFLOP/s", "frac": flops / (k_us * 1e-6) / 1e12 / peak, "traffic": None, "kernel_us": k_us,
+                     "algorithmic_flops_per_launch": flops},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +141,8 @@ def main():
                     help="depth override for kernel tuning runs (0 = the configuration's own depth, which the metric needs)")
     ap.add_argument("--two-calls", action="store_true",
                     help="run flowmm_plan then flowmm_merge instead of the one-call flowmm_plan_merge")
+    ap.add_argument("--flow-exact", action="store_true",
+                    help="time flowmm_flow_exact (the interaction ratio over all prompt queries) instead of the merge path")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -122,6 +164,8 @@ def main():
     fb.load(build_if_missing=False)
     wl = workloads.config(args.config, n_layers=args.layers or None)
     dev = "cuda:0"
+    if args.flow_exact:
+        return bench_flow_exact(args, wl, dev)
     K, V, Q = fb.upload_workload(wl, dev)
     params = fb.Params.from_workload(wl)
     bufs = fb.DeviceBuffers(params, dev)
