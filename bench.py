@@ -31,7 +31,7 @@ def algorithmic_bytes(wl):
     d, G, W = wl.head_dim, wl.group, wl.window
     units = wl.n_layers * wl.n_kv_heads
     tot = {k: 0 for k in ("whole_pass", "score_stats", "score_colsum", "match", "merge_tasks",
-                          "select", "merge_csr", "unit_plan", "unit_merge", "unit_stream_plan", "unit_stream_merge")}
+                          "select", "merge_csr", "unit_plan", "unit_merge", "unit_flow_merge")}
     for L, B in zip(wl.seqlens, wl.budgets):
         row = d * s
         tot["whole_pass"] += units * (3 * L * row + 2 * B * row + G * W * row + 12 * L)
@@ -48,10 +48,7 @@ def algorithmic_bytes(wl):
         # keeps the unit's keys in registers, so its measured traffic is about one K less than this
         tot["unit_plan"] += units * (2 * L * row + G * W * row + 12 * L + 4 * B)
         tot["unit_merge"] += units * (2 * L * row + 2 * B * row + 4 * L + 4 * B)  # K, V rows, assign, kept in; compacted out
-        tot["unit_stream_plan"] = tot["unit_plan"]
-        # the one kernel that takes a unit from its keys to its merged rows: the whole-pass figure less the
-        # round trip of the importances (written for the caller, not read back)
-        tot["unit_stream_merge"] += units * (3 * L * row + 2 * B * row + G * W * row + 8 * L + 4 * B)
+        tot["unit_flow_merge"] = tot["unit_merge"]  # the merge launch that also settles the layer strategies
     return tot
 
 
