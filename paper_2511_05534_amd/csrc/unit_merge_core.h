@@ -171,23 +171,38 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   const int gid = wave * RPL + rg;
 
   // pivots nobody merges into: bit copies (needs no member list, so it runs before the barrier).
-  // All loads of a pass are issued before the first store: nothing in between is conditional
-  // (a lane without a row repeats the last one), so the compiler has no reason to wait in between.
-  for (int base = 0; base < n_copy; base += kGroups * U) {
-    int slotv[U];
-    uint4 kc[U], vc[U];
+  // Full passes first: U rows per group with nothing conditional between the loads, so that they
+  // are all in flight before the first store; then the rest one row at a time.  (The rows pass
+  // through a native vector type: arrays of the uint4 class would be kept in scratch memory.)
+  {
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t *Kc = reinterpret_cast<const u32x4_t *>(K), *Vc = reinterpret_cast<const u32x4_t *>(V);
+    u32x4_t *Koc = reinterpret_cast<u32x4_t *>(Ko), *Voc = reinterpret_cast<u32x4_t *>(Vo);
+    int idx = gid;
+    for (; idx + (U - 1) * kGroups < n_copy; idx += U * kGroups) {
+      int slotv[U];
+      u32x4_t kc[U], vc[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) slotv[u] = copies[min(base + u * kGroups + gid, n_copy - 1)];
+      for (int u = 0; u < U; ++u) slotv[u] = copies[idx + u * kGroups];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int tok = lds_kept[slotv[u]];
-      kc[u] = K[(long long)tok * sh.ks_tok + ch];
-      vc[u] = V[(long long)tok * sh.ks_tok + ch];
+      for (int u = 0; u < U; ++u) {
+        const int tok = lds_kept[slotv[u]];
+        kc[u] = Kc[(long long)tok * sh.ks_tok + ch];
+        vc[u] = Vc[(long long)tok * sh.ks_tok + ch];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        Koc[(long long)slotv[u] * LPR + ch] = kc[u];
+        Voc[(long long)slotv[u] * LPR + ch] = vc[u];
+      }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      Ko[(long long)slotv[u] * LPR + ch] = kc[u];
-      Vo[(long long)slotv[u] * LPR + ch] = vc[u];
+    for (; idx < n_copy; idx += kGroups) {
+      const int slot = copies[idx];
+      const int tok = lds_kept[slot];
+      const u32x4_t kc = Kc[(long long)tok * sh.ks_tok + ch];
+      const u32x4_t vc = Vc[(long long)tok * sh.ks_tok + ch];
+      Koc[(long long)slot * LPR + ch] = kc;
+      Voc[(long long)slot * LPR + ch] = vc;
     }
   }
   __syncthreads();
