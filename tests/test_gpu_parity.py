@@ -40,6 +40,16 @@ SMALL_CASES = {
     "unit_two_row_blocks_gqa": dict(Hq=4, Hkv=2, W=32, spans=((20, 600, 40),), pct=(12,)),
     "shortest": dict(Hq=1, Hkv=1, W=1, spans=((1,),), budgets=(1,), n_layers=1),
     "tiny_3_tokens": dict(Hq=2, Hkv=1, W=2, spans=((1, 2),), budgets=(2,), n_layers=1),
+    # the limits of the unit-resident kernels: 1024 tokens, 256 pivots, 8 sequences, 32 spans; and one step beyond
+    "unit_limit_1024_tokens_256_pivots": dict(Hq=2, Hkv=1, W=32, spans=((100, 800, 124),), budgets=(256,), n_layers=1),
+    "one_token_beyond_the_unit_limit": dict(Hq=2, Hkv=1, W=32, spans=((100, 800, 125),), budgets=(256,), n_layers=1),
+    "unit_twelve_tiles": dict(Hq=2, Hkv=2, W=32, spans=((30, 300, 54),), pct=(15,), n_layers=1),
+    "unit_batch_of_8": dict(Hq=2, Hkv=1, W=16, n_layers=1, pct=(10, 20, 5, 10, 20, 5, 10, 20),
+                            spans=((30, 100, 20), (20, 200, 30), (40, 60, 17), (25, 300, 33), (16,), (50, 400, 50),
+                                   (10, 90, 16), (33, 150, 47))),
+    "unit_32_spans": dict(Hq=2, Hkv=1, W=16, n_layers=1, pct=(12,), spans=(tuple([20, 10] * 15 + [25, 17]),)),
+    "more_spans_than_the_unit_path_takes": dict(Hq=2, Hkv=1, W=16, n_layers=1, pct=(12,),
+                                                spans=(tuple([20, 10] * 16 + [25, 17]),)),
 }
 
 
