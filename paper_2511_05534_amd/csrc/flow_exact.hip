@@ -194,19 +194,27 @@ __global__ __launch_bounds__(kFThreads, 2) void flow_exact_kernel(Ctx c, FlowExa
   if (threadIdx.x == 0) a.part[((long long)l * sh.Hq + h) * a.qtiles_total + x] = lds_red[0];
 }
 
-// rho of every (layer, sequence): heads and query tiles added in a fixed order
-__global__ __launch_bounds__(64) void flow_exact_finish_kernel(Ctx c, FlowExactArgs a) {
+// rho of every (layer, sequence): thread h adds the query tiles of head h in order, thread 0 then the heads in order
+__global__ __launch_bounds__(256) void flow_exact_finish_kernel(Ctx c, FlowExactArgs a) {
+  __shared__ float lds_head[256];
   const Shape &sh = c.sh;
   const int b = blockIdx.x, l = blockIdx.y;
-  if (threadIdx.x != 0) return;
   const int *cu = c.meta + c.meta[MW_OFF_CU_FLOWQ];
   const SeqInfo s = load_seq(c.meta, b);
   float acc = 0.f;
-  for (int h = 0; h < sh.Hq; ++h) {
-    float hs = 0.f;
-    for (int x = cu[b]; x < cu[b + 1]; ++x) hs += a.part[((long long)l * sh.Hq + h) * a.qtiles_total + x];
-    acc += hs / (float)s.L;
+  for (int h0 = 0; h0 < sh.Hq; h0 += 256) {
+    const int h = h0 + threadIdx.x;
+    if (h < sh.Hq) {
+      float hs = 0.f;
+      for (int x = cu[b]; x < cu[b + 1]; ++x) hs += a.part[((long long)l * sh.Hq + h) * a.qtiles_total + x];
+      lds_head[threadIdx.x] = hs / (float)s.L;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (int i = 0; i < min(256, sh.Hq - h0); ++i) acc += lds_head[i];
+    __syncthreads();
   }
+  if (threadIdx.x != 0) return;
   const float rho = acc / (float)sh.Hq;
   a.rho[l * sh.batch + b] = rho;
   a.mode[l * sh.batch + b] = (rho > sh.theta) != (sh.invert_flow != 0) ? 1 : 0;
@@ -225,7 +233,7 @@ hipError_t launch_flow_exact_t(const Ctx &c, const FlowExactArgs &a) {
     ProfScope ps(c.stream, KID_FLOW_EXACT);
     flow_exact_kernel<BF16, D><<<dim3(a.qtiles_total, c.sh.Hq, c.sh.n_layers), kFThreads, lds, c.stream>>>(c, a);
   }
-  flow_exact_finish_kernel<<<dim3(c.sh.batch, c.sh.n_layers), 64, 0, c.stream>>>(c, a);
+  flow_exact_finish_kernel<<<dim3(c.sh.batch, c.sh.n_layers), 256, 0, c.stream>>>(c, a);
   return hipGetLastError();
 }
 
