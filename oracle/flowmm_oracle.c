@@ -32,6 +32,9 @@
  *                (cross-modal merging exactly where the rule says intra-modal);
  *   fmo_merge_weighted        - f_merge/g_merge as a similarity-weighted mean: the pivot
  *                counts 1, a member counts max(u, 0) with u its cosine to the pivot.
+ *   fmo_decode_attention      - one decode step of attention (the attention-output equation of
+ *                the Preliminary section, o_t = softmax(q_t K^T / sqrt d) V) over a compacted cache:
+ *                what the paper's decoding-latency table exercises on the compressed cache.
  *   ("Without sensitivity-adaptive matching" is tau = +inf; "without information flow
  *   guidance" is a theta below 0 or above 1; neither needs code of its own.)
  */
@@ -248,6 +251,33 @@ void fmo_merge_weighted(int L, int d, int B, const float *K, const float *V, con
       Vout[(size_t)s * d + c] /= wsum[s];
     }
   }
+}
+
+/* One KV head of one sequence: q [G][d] (the G query heads that read this KV head), Kc, Vc [B][d]
+ * (the compacted cache).  out [G][d] = softmax_s(scale * <q_g, Kc_s>) Vc, in double. */
+void fmo_decode_attention(int G, int B, int d, double scale, const float *q, const float *Kc, const float *Vc,
+                          double *out) {
+  double *p = (double *)malloc(sizeof(double) * (size_t)B);
+  for (int g = 0; g < G; ++g) {
+    double mx = -INFINITY;
+    for (int s = 0; s < B; ++s) {
+      double dot = 0.0;
+      for (int c = 0; c < d; ++c) dot += (double)q[(size_t)g * d + c] * (double)Kc[(size_t)s * d + c];
+      p[s] = scale * dot;
+      if (p[s] > mx) mx = p[s];
+    }
+    double z = 0.0;
+    for (int s = 0; s < B; ++s) {
+      p[s] = exp(p[s] - mx);
+      z += p[s];
+    }
+    for (int c = 0; c < d; ++c) {
+      double acc = 0.0;
+      for (int s = 0; s < B; ++s) acc += p[s] * (double)Vc[(size_t)s * d + c];
+      out[(size_t)g * d + c] = acc / z;
+    }
+  }
+  free(p);
 }
 
 /* Round-to-nearest-even of doubles to the output dtype (0 = fp32, 1 = bf16), result as float. */

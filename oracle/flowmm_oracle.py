@@ -136,6 +136,19 @@ def merge_weighted(K, V, kept_idx, assign):
     return ko, vo, nm, ws
 
 
+def decode_attention(q, Kc, Vc, scale=None):
+    """q [G][d], Kc, Vc [B][d] -> out [G][d] float64: one decode step of attention over a compacted cache."""
+    q, Kc, Vc = _f32(q), _f32(Kc), _f32(Vc)
+    G, d = q.shape
+    B = Kc.shape[0]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((G, d), dtype=np.float64)
+    _load().fmo_decode_attention(G, B, d, C.c_double(scale), _p(q, C.c_float), _p(Kc, C.c_float), _p(Vc, C.c_float),
+                                 _p(out, C.c_double))
+    return out
+
+
 def round_output(x, dtype: str):
     """Nearest-even rounding of float64 to the cache dtype ("bf16" | "f32"); float32 array."""
     x = _f64(x)

@@ -421,6 +421,35 @@ def test_weighted_merge_special_cases(oracle):
     assert (ko[0] <= K.max(axis=0) + 1e-12).all() and (ko[0] >= K.min(axis=0) - 1e-12).all()
 
 
+# --------------------------------------------------------------------------------------
+# decode attention over the compacted cache
+# --------------------------------------------------------------------------------------
+def test_decode_attention_matches_dense_softmax_and_closed_forms(oracle):
+    rng = np.random.default_rng(77)
+    G, B, d = 3, 37, 16
+    q = rng.standard_normal((G, d)).astype(np.float32)
+    Kc = rng.standard_normal((B, d)).astype(np.float32)
+    Vc = rng.standard_normal((B, d)).astype(np.float32)
+    out = oracle.decode_attention(q, Kc, Vc)
+    logits = q.astype(np.float64) @ Kc.astype(np.float64).T / np.sqrt(d)
+    w = np.exp(logits - logits.max(axis=1, keepdims=True))
+    w /= w.sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(out, w @ Vc.astype(np.float64), rtol=1e-12, atol=1e-14)
+    # a zero query attends uniformly: the mean of the value rows
+    np.testing.assert_allclose(oracle.decode_attention(np.zeros((1, d), np.float32), Kc, Vc)[0],
+                               Vc.astype(np.float64).mean(axis=0), rtol=1e-13)
+    # a single cached row is returned as it is, whatever the query
+    np.testing.assert_allclose(oracle.decode_attention(q, Kc[:1], Vc[:1]), np.repeat(Vc[:1].astype(np.float64), G, 0))
+    # a key far more aligned with the query than the rest takes all the mass
+    Kb = Kc.copy()
+    Kb[5] = 100.0 * q[0]
+    np.testing.assert_allclose(oracle.decode_attention(q[:1], Kb, Vc)[0], Vc[5], atol=1e-9)
+    # an explicit scale of 0 is uniform attention again; permuting the cache rows changes nothing
+    np.testing.assert_allclose(oracle.decode_attention(q, Kc, Vc, scale=0.0)[1], Vc.astype(np.float64).mean(axis=0), rtol=1e-13)
+    perm = rng.permutation(B)
+    np.testing.assert_allclose(oracle.decode_attention(q, Kc[perm], Vc[perm]), out, rtol=1e-12, atol=1e-14)
+
+
 def test_rounding_to_bf16_is_nearest_even(oracle):
     # bf16 has 8 significant bits: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0)
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -30, -3.0, 0.0,
