@@ -148,6 +148,17 @@ flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K, const voi
                                 float *rho, int32_t *mode, void *workspace, size_t workspace_bytes,
                                 void *stream);
 
+/* One decode step of attention over the compacted cache that flowmm_merge wrote (the attention
+ * of the paper's Preliminary section, o = softmax(scale * q K^T) V, on the merged rows): for every
+ * layer l, query head h and sequence b
+ *   out[l][h][b] = sum_s softmax_s(scale * <q[l][h][b], K_c[l][kv(h)][s]>) V_c[l][kv(h)][s],
+ * s over the B_b slots of sequence b.  q, out: device, [Lyr][Hq][batch][d] contiguous, dtype of the
+ * cache; K_c, V_c: [Lyr][Hkv][SB][d] as flowmm_merge lays them out.  p as for the other calls (its
+ * budgets give the slot ranges; spans, window and tau are validated but not used); workspace and
+ * its size as reported by flowmm_plan_sizes.  Every merged row is read once. */
+flowmm_status flowmm_decode_attention(const flowmm_params *p, const void *q, const void *K_c, const void *V_c,
+                                      void *out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Message of the last failing call on this thread (static storage, never NULL). */
 const char *flowmm_last_error(void);
 

@@ -20,7 +20,7 @@ FLOWMM_FLAG_GENERIC_PATH, FLOWMM_FLAG_INVERT_FLOW, FLOWMM_FLAG_WEIGHTED_MERGE = 
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
 EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_flow_exact",
-           "flowmm_last_error",
+           "flowmm_decode_attention", "flowmm_last_error",
            "flowmm_profile_kernel_count", "flowmm_profile_kernel_name", "flowmm_profile_select",
            "flowmm_profile_collect")
 
@@ -79,6 +79,8 @@ def load(build_if_missing: bool = True):
         lib.flowmm_flow_exact.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                           C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.flowmm_flow_exact.restype = C.c_int
+        lib.flowmm_decode_attention.argtypes = [C.POINTER(flowmm_params)] + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]
+        lib.flowmm_decode_attention.restype = C.c_int
         for f in (lib.flowmm_plan_sizes, lib.flowmm_plan, lib.flowmm_merge, lib.flowmm_plan_merge, lib.flowmm_profile_collect,
                   lib.flowmm_profile_kernel_count):
             f.restype = C.c_int
@@ -180,6 +182,13 @@ def flowmm_flow_exact(params: Params, K: int, Q_full: int, q_strides: Tuple[int,
                                     C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
+def flowmm_decode_attention(params: Params, q: int, K_c: int, V_c: int, out: int, workspace: int,
+                            workspace_bytes: int, stream: int = 0):
+    _check(load().flowmm_decode_attention(C.byref(params.c), C.c_void_p(q), C.c_void_p(K_c), C.c_void_p(V_c),
+                                          C.c_void_p(out), C.c_void_p(workspace), C.c_size_t(workspace_bytes),
+                                          C.c_void_p(stream)))
+
+
 def flowmm_profile_select(names: str = ""):
     load().flowmm_profile_select(names.encode())
 
@@ -250,6 +259,13 @@ class DeviceBuffers:
         Hq, T, d = Q_full.shape[1:]
         flowmm_flow_exact(self.params, K.data_ptr(), Q_full.data_ptr(), (Hq * T * d, T * d, d), self.rho.data_ptr(),
                           self.mode.data_ptr(), self.workspace.data_ptr(), self.workspace_bytes, stream)
+
+    def decode_attention(self, q, out, K_c=None, V_c=None, stream: int = 0):
+        """q, out [Lyr][Hq][batch][d] contiguous; attends over self.K_out / self.V_out unless others are given."""
+        K_c = self.K_out if K_c is None else K_c
+        V_c = self.V_out if V_c is None else V_c
+        flowmm_decode_attention(self.params, q.data_ptr(), K_c.data_ptr(), V_c.data_ptr(), out.data_ptr(),
+                                self.workspace.data_ptr(), self.workspace_bytes, stream)
 
     def merge(self, K, V, stream: int = 0):
         flowmm_merge(self.params, self.plan_ptrs, K.data_ptr(), V.data_ptr(), self.K_out.data_ptr(),

@@ -200,6 +200,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   rg.part_stats = off; off += align256((size_t)units * sh.tiles_score * sh.R_pad * sizeof(float2));
   rg.rowstat = off; off += align256((size_t)units * batch * sh.R_pad * sizeof(float2));
   rg.cross_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.tiles_score * 4);
+  rg.decode_part = off; off += align256((size_t)sh.n_layers * sh.Hq * batch * kDecodeMaxSplits * (sh.d + 2) * 4);
   rg.flow_part = off; off += align256((size_t)sh.n_layers * sh.Hq * sh.flowq_total * 4);
   if (!sh.unit_path) {
     rg.pl_slot = off; off += align256((size_t)units * 2 * sh.SBP * 4);
@@ -437,6 +438,31 @@ FLOWMM_API flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K
   hipError_t e;
   if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
   if ((e = launch_flow_exact(c, a)) != hipSuccess) return hip_fail(e, "exact flow-ratio kernels");
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_decode_attention(const flowmm_params *p, const void *q, const void *K_c, const void *V_c,
+                                      void *out, void *workspace, size_t workspace_bytes, void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (!q || !K_c || !V_c || !out || !workspace) return fail(FLOWMM_EINVAL, "q, K_c, V_c, out and workspace must not be NULL");
+  if (misaligned(q) || misaligned(K_c) || misaligned(V_c) || misaligned(out) || misaligned(workspace))
+    return fail(FLOWMM_EINVAL, "q, K_c, V_c, out and workspace must be 16-byte aligned");
+  if (workspace_bytes < lo.workspace_bytes)
+    return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
+  flowmm_plan_buffers none;
+  std::memset(&none, 0, sizeof(none));
+  Ctx c;
+  fill_ctx(c, lo, &none, workspace, stream);
+  DecodeArgs a;
+  a.q = q; a.K_c = K_c; a.V_c = V_c; a.out = out;
+  a.part = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + lo.rg.decode_part);
+  a.splits = decode_splits(lo.sh);
+  a.g0 = 0;
+  hipError_t e;
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), false)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_decode_attention(c, a)) != hipSuccess) return hip_fail(e, "decode attention kernels");
   return FLOWMM_OK;
 }
 

@@ -53,6 +53,18 @@ struct FlowExactArgs {
 };
 hipError_t launch_flow_exact(const Ctx &c, const FlowExactArgs &a);
 
+// arguments of the decode-step attention over the compacted cache
+struct DecodeArgs {
+  const void *q;               // [Lyr][Hq][batch][d]
+  const void *K_c, *V_c;       // [Lyr][Hkv][SB][d] merged rows
+  void *out;                   // [Lyr][Hq][batch][d]
+  float *part;                 // [Lyr][Hq][batch][splits][d + 2] partial (weighted V, max, sum) per slot range
+  int splits;                  // slot ranges per sequence
+  int g0;                      // first query head (inside its kv group) of the current launch
+};
+int decode_splits(const Shape &sh);
+hipError_t launch_decode_attention(const Ctx &c, const DecodeArgs &a);
+
 constexpr int kMetaChunkWords = 960;
 struct MetaChunk { int w[kMetaChunkWords]; };
 

@@ -51,6 +51,7 @@ constexpr int match_tile_tokens(bool bf16) { return kMatchWaves * 32 * match_sub
 // packed pivot rows staged in LDS at a time: 32 KB worth, 128 rows at most (nch = 16-byte chunks per row)
 constexpr int match_tile_rows(int nch) { return 2048 / nch < 128 ? 2048 / nch : 128; }
 constexpr int kFlowQueryTile = 256;                          // query rows per workgroup of the exact flow ratio
+constexpr int kDecodeMaxSplits = 32;                         // slot ranges per sequence of the decode-step attention
 constexpr int kTaskChunk = 32;                               // members summed by one wave task
 constexpr int kCsrWaves = 16;                                // waves of the CSR-building workgroup
 constexpr int kFoldGroups = 4;                               // workgroups per (sequence, kv head, layer) that fold split slots
@@ -85,6 +86,7 @@ struct InlineMeta {
 struct Regions {
   size_t meta, mod, cls_order;                              // both calls
   size_t part_stats, rowstat, cross_part;                   // plan: score
+  size_t decode_part;                                       // decode attention: [Lyr][Hq][batch][kDecodeMaxSplits][d+2]
   size_t flow_part;                                         // exact flow ratio: [Lyr][Hq][flowq_total]
   size_t pl_slot, pl_tok, pl_w, pl_n, pack;                 // plan: match
   size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials, partial_w;  // merge

@@ -13,7 +13,7 @@ namespace {
 
 const char *const kNames[KID_COUNT] = {"meta_upload", "expand_modality", "score_stats", "score_combine",
                                        "score_colsum", "select", "match", "merge_csr", "merge_tasks",
-                                       "merge_fold",                                        "unit_plan", "unit_match", "unit_merge", "unit_flow_merge", "flow_exact"};
+                                       "merge_fold",                                        "unit_plan", "unit_match", "unit_merge", "unit_flow_merge", "flow_exact", "decode_partial", "decode_combine"};
 
 struct Record { int id; hipEvent_t start, stop; };
 

@@ -4,7 +4,7 @@ import pytest
 
 from paper_2511_05534_amd import workloads as wl
 
-from parity_utils import Report, check_layer, run_gpu, upload
+from parity_utils import ATOL_OUT, Report, bf16_ulp, check_layer, run_gpu, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -172,6 +172,57 @@ def test_flow_exact_matches_the_literal_ratio(oracle, name):
                 assert abs(rho_g[l, b] - rho_o) <= 2e-4 * max(rho_o, 1e-6) + 1e-7, (l, b, rho_g[l, b], rho_o)
                 if abs(rho_o - theta) > 1e-3 * abs(theta):
                     assert mode_g[l, b] == mode_o
+
+
+DECODE_CASES = {
+    "mha_small": dict(Hq=2, Hkv=2, spans=((40, 150, 30),)),
+    "gqa_2": dict(Hq=4, Hkv=2, spans=((37, 411, 83),)),
+    "gqa_7_like_qwen2": dict(Hq=7, Hkv=1, W=8, spans=((50, 400, 62),), pct=(20,)),
+    "gqa_12_two_batches_of_heads": dict(Hq=12, Hkv=1, W=4, spans=((30, 200, 26),), pct=(20,)),
+    "d64": dict(Hq=2, Hkv=2, d=64, W=24, spans=((50, 500, 77),)),
+    "f32_d64": dict(dtype="f32", Hq=4, Hkv=4, d=64, W=16, spans=((32, 256, 32),), pct=(20,)),
+    "f32_d128": dict(dtype="f32", Hq=2, Hkv=1, d=128, W=8, spans=((20, 200, 19),)),
+    "many_slots_split_ranges": dict(Hq=4, Hkv=1, W=32, spans=((100, 2500, 50, 1600, 50),), pct=(30,), n_layers=1),
+    "batch_of_3": dict(Hq=4, Hkv=2, W=16, spans=((30, 260, 40), (64, 700, 69), (20, 100, 17)), pct=(10, 20, 5)),
+    "one_slot": dict(Hq=1, Hkv=1, W=1, spans=((1,),), budgets=(1,), n_layers=1),
+}
+
+
+@pytest.mark.parametrize("name", list(DECODE_CASES))
+def test_decode_attention_over_the_compacted_cache(oracle, name):
+    """flowmm_decode_attention on the cache flowmm_plan_merge has just written, against the oracle's
+    softmax attention over the same merged rows (max-abs error as for the merged rows themselves)."""
+    import torch
+    w = small(name, **DECODE_CASES[name])
+    print(f"case {name}: L={w.seqlens} B={w.budgets} dtype={w.dtype} G={w.group}", flush=True)
+    from paper_2511_05534_amd import binding as fb
+    K, V, Q = upload(w)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    params = fb.Params.from_workload(w)
+    bufs = fb.DeviceBuffers(params)
+    bufs.plan_merge(K, V, Q)
+    gen = torch.Generator(device="cuda:0").manual_seed(5)
+    q = torch.randn((w.n_layers, w.n_q_heads, w.batch, w.head_dim), generator=gen, device="cuda:0").to(tdt)
+    out = torch.full_like(q, float("nan"))
+    bufs.decode_attention(q, out, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    Kc, Vc = bufs.K_out.float().cpu().numpy(), bufs.V_out.float().cpu().numpy()
+    qn, got = q.float().cpu().numpy(), out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    cuk, G = w.cu_kept, w.group
+    worst = 0.0
+    for l in range(w.n_layers):
+        for g in range(w.n_kv_heads):
+            for b in range(w.batch):
+                rows = slice(int(cuk[b]), int(cuk[b + 1]))
+                want = oracle.decode_attention(qn[l, g * G:(g + 1) * G, b], Kc[l, g, rows], Vc[l, g, rows])
+                err = np.abs(got[l, g * G:(g + 1) * G, b] - want)
+                tol = np.full(want.shape, ATOL_OUT[w.dtype])
+                if w.dtype == "bf16":
+                    tol = np.maximum(tol, bf16_ulp(want))
+                assert (err <= tol).all(), (l, g, b, err.max())
+                worst = max(worst, float(err.max()))
+    print(f"max abs error {worst:.2e}", flush=True)
 
 
 def test_one_call_equals_two_calls():
