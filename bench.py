@@ -128,6 +128,52 @@ def bench_flow_exact(args, wl, dev):
     }))
 
 
+def bench_decode(args, wl, dev):
+    """Decode-step attention over the compacted cache at the budgets of the paper's latency table
+    (shape of the trend only: attention over the cache, not a model's whole decode step)."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    s = 2 if wl.dtype == "bf16" else 4
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for pct in (100, 50, 35, 20, 5):
+        budgets = [min(L, max(wl.window, (L * pct + 50) // 100)) for L in wl.seqlens]
+        params = fb.Params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.seqlens, budgets,
+                           wl.spans, wl.window, wl.theta, wl.tau)
+        bufs = fb.DeviceBuffers(params, dev)
+        bufs.K_out.copy_(torch.randn(bufs.K_out.shape, generator=gen, device=dev).to(tdt))
+        bufs.V_out.copy_(torch.randn(bufs.V_out.shape, generator=gen, device=dev).to(tdt))
+        q = torch.randn((wl.n_layers, wl.n_q_heads, wl.batch, wl.head_dim), generator=gen, device=dev).to(tdt)
+        out = torch.empty_like(q)
+        for _ in range(args.warmup):
+            bufs.decode_attention(q, out, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            bufs.decode_attention(q, out, stream=stream)
+        torch.cuda.synchronize()
+        us = 1e6 * (time.perf_counter() - t0) / args.steps
+        nbytes = 2 * wl.n_layers * wl.n_kv_heads * sum(budgets) * wl.head_dim * s + 2 * q.numel() * s
+        rows.append({"budget_pct": pct, "slots": budgets, "us_per_step": us, "cache_bytes": nbytes,
+                     "GBs": nbytes / (us * 1e-6) / 1e9, "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS})
+        del bufs
+    full = rows[0]
+    print(json.dumps({
+        "metric": "decode-step attention over the compacted cache, latency per step by budget",
+        "value": full["us_per_step"] / rows[-1]["us_per_step"], "unit": "x faster at 5 % budget than at 100 %",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rows[-1]["us_per_step"] / 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {wl.name}", "layers": wl.n_layers, "q_heads": wl.n_q_heads,
+                   "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "seqlens": wl.seqlens,
+                   "entry_point": "flowmm_decode_attention"},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial", "achieved": full["GBs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": full["frac_of_hbm_peak"], "traffic": None},
+        "by_budget": rows,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +186,8 @@ def main():
                     help="run flowmm_plan then flowmm_merge instead of the one-call flowmm_plan_merge")
     ap.add_argument("--flow-exact", action="store_true",
                     help="time flowmm_flow_exact (the interaction ratio over all prompt queries) instead of the merge path")
+    ap.add_argument("--decode", action="store_true",
+                    help="time flowmm_decode_attention over compacted caches of this configuration at 100/50/35/20/5 %% budget")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -163,6 +211,8 @@ def main():
     dev = "cuda:0"
     if args.flow_exact:
         return bench_flow_exact(args, wl, dev)
+    if args.decode:
+        return bench_decode(args, wl, dev)
     K, V, Q = fb.upload_workload(wl, dev)
     params = fb.Params.from_workload(wl)
     bufs = fb.DeviceBuffers(params, dev)
