@@ -30,6 +30,22 @@ __device__ __forceinline__ void fold_state(float &m, float &z, float *acc, int n
   m = M;
 }
 
+// sum over the LPR lanes that share a row, left in every one of them.  Sixteen lanes are one DPP row:
+// four rotate-and-add steps on the vector unit; other widths go through the lane permute.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+  if constexpr (LPR == 16) {
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));  // row_ror:8
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xf, 0xf, false));  // row_ror:4
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x122, 0xf, 0xf, false));  // row_ror:2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x121, 0xf, 0xf, false));  // row_ror:1
+  } else {
+#pragma unroll
+    for (int o = LPR / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  }
+  return v;
+}
+
 template <bool BF16, int D, int GP>
 __global__ __launch_bounds__(kDThreads) void decode_partial_kernel(Ctx c, DecodeArgs a) {
   using CF = Cfg<BF16, D>;
@@ -80,28 +96,42 @@ __global__ __launch_bounds__(kDThreads) void decode_partial_kernel(Ctx c, Decode
       kc[u] = Kc[(long long)r * LPR + ch];
       vc[u] = Vc[(long long)r * LPR + ch];
     }
+    // the logits of the U rows for every head, then one rescale of the running state per head and trip
+    float fv[U][EPC];
+    float sl[GP][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float fk[EPC], fv[EPC];
+      float fk[EPC];
       chunk_to_floats<BF16>(kc[u], fk);
-      chunk_to_floats<BF16>(vc[u], fv);
+      chunk_to_floats<BF16>(vc[u], fv[u]);
       const bool real = r0 + u * kGroups < s1;
 #pragma unroll
       for (int g = 0; g < GP; ++g) {
         float dot = 0.f;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) dot = fmaf(fk[e], q[g][e], dot);
-#pragma unroll
-        for (int o = LPR / 2; o >= 1; o >>= 1) dot += __shfl_xor(dot, o, 64);
-        const float s = real ? dot * cl : -INFINITY;
-        const float M = fmaxf(m[g], s);
-        const float Ms = M == -INFINITY ? 0.f : M;
-        const float sc = fast_exp2(m[g] - Ms), p = fast_exp2(s - Ms);
-        z[g] = z[g] * sc + p;
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(p, fv[e], acc[g][e] * sc);
-        m[g] = M;
+        dot = group_sum<LPR>(dot);
+        sl[g][u] = real ? dot * cl : -INFINITY;
       }
+    }
+#pragma unroll
+    for (int g = 0; g < GP; ++g) {
+      float M = m[g];
+#pragma unroll
+      for (int u = 0; u < U; ++u) M = fmaxf(M, sl[g][u]);
+      const float Ms = M == -INFINITY ? 0.f : M;
+      const float sc = fast_exp2(m[g] - Ms);
+      z[g] *= sc;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[g][e] *= sc;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float p = fast_exp2(sl[g][u] - Ms);
+        z[g] += p;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[g][e] = fmaf(p, fv[u][e], acc[g][e]);
+      }
+      m[g] = M;
     }
   }
 
