@@ -94,13 +94,32 @@ def test_pointer_checks_happen_before_any_launch():
         (lambda: fb.flowmm_merge(p, plan, good, 1 << 40, good + 256, 1 << 41, good, ws), "overlap"),
         (lambda: fb.flowmm_merge(p, plan, good, 1 << 40, 1 << 41, 1 << 41, 1 << 42, ws), "overlap"),
     ]
+    far = [1 << 40, 1 << 41, 1 << 42, 1 << 43]
+    qs = (4 * 500 * 128, 500 * 128, 128)
+    cases += [
+        (lambda: fb.flowmm_plan_merge(p, good, far[0], 0, plan, far[1], far[2], good, ws), "NULL"),
+        (lambda: fb.flowmm_plan_merge(p, good, far[0], far[3], plan, far[1], 0, good, ws), "NULL"),
+        (lambda: fb.flowmm_plan_merge(p, good, far[0], far[3], plan, far[1], far[1] + 256, good, ws), "overlap"),
+        (lambda: fb.flowmm_plan_merge(p, good, far[0], far[3], [good, good, good, 0, good, good], far[1], far[2], good, ws),
+         "plan->kept_idx"),
+        (lambda: fb.flowmm_flow_exact(p, good, 0, qs, good, good, good, ws), "NULL"),
+        (lambda: fb.flowmm_flow_exact(p, good, far[0], qs, good + 2, good, good, ws), "4-byte"),
+        (lambda: fb.flowmm_flow_exact(p, good, far[0], (qs[0], qs[1], 100), good, good, good, ws), "stride"),
+        (lambda: fb.flowmm_flow_exact(p, good, far[0], (qs[0], qs[1], 132), good, good, good, ws), "16 bytes"),
+        (lambda: fb.flowmm_decode_attention(p, good, far[0], far[1], 0, good, ws), "NULL"),
+        (lambda: fb.flowmm_decode_attention(p, good + 4, far[0], far[1], far[2], good, ws), "aligned"),
+    ]
     for call, word in cases:
         with pytest.raises(fb.FlowMMError) as ei:
             call()
         assert ei.value.status == fb.FLOWMM_EINVAL and word in ei.value.message, ei.value.message
-    with pytest.raises(fb.FlowMMError) as ei:
-        fb.flowmm_plan(p, good, good, plan, good, ws - 1)
-    assert ei.value.status == fb.FLOWMM_EWORKSPACE
+    for call in (lambda: fb.flowmm_plan(p, good, good, plan, good, ws - 1),
+                 lambda: fb.flowmm_plan_merge(p, good, far[0], far[3], plan, far[1], far[2], good, ws - 1),
+                 lambda: fb.flowmm_flow_exact(p, good, far[0], qs, good, good, good, ws - 1),
+                 lambda: fb.flowmm_decode_attention(p, good, far[0], far[1], far[2], good, ws - 1)):
+        with pytest.raises(fb.FlowMMError) as ei:
+            call()
+        assert ei.value.status == fb.FLOWMM_EWORKSPACE
 
 
 def test_last_error_is_never_null():
