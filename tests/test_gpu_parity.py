@@ -225,6 +225,39 @@ def test_decode_attention_over_the_compacted_cache(oracle, name):
     print(f"max abs error {worst:.2e}", flush=True)
 
 
+def test_hip_graph_replay_equals_eager():
+    """The library neither allocates nor synchronises, so its calls can be captured into a HIP graph:
+    every replay (with eager work and synchronisation in between) must reproduce the eager result."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    for name, flags in (("graph_unit", 0), ("graph_generic", 1)):
+        w = small(name, Hq=4, Hkv=2, spans=((37, 411, 83),), n_layers=3)
+        K, V, Q = upload(w)
+        params = fb.Params.from_workload(w, flags=flags)
+        eager = fb.DeviceBuffers(params)
+        eager.plan_merge(K, V, Q, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        want = {n: getattr(eager, n).clone() for n in fb.PLAN_FIELDS + ("K_out", "V_out")}
+        bufs = fb.DeviceBuffers(params)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            bufs.plan_merge(K, V, Q, side.cuda_stream)  # warm-up outside the capture (function attributes, lazy loading)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            bufs.plan_merge(K, V, Q, torch.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            for n in fb.PLAN_FIELDS + ("K_out", "V_out"):
+                getattr(bufs, n).fill_(0)
+            scratch = torch.randn(1 << 20, device="cuda:0").sum().item()  # unrelated eager work and a synchronisation
+            graph.replay()
+            torch.cuda.synchronize()
+            for n in fb.PLAN_FIELDS + ("K_out", "V_out"):
+                assert torch.equal(getattr(bufs, n), want[n]), (name, rep, n)
+
+
 def test_one_call_equals_two_calls():
     """flowmm_plan_merge against flowmm_plan + flowmm_merge: the same decisions up to the last bits of
     the importances (the two spread the key tiles over their waves differently), and bit-identical
