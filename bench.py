@@ -182,6 +182,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the metric's configuration)")
     ap.add_argument("--layers", type=int, default=0,
                     help="depth override for kernel tuning runs (0 = the configuration's own depth, which the metric needs)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays of it (the library neither allocates nor "
+                         "synchronises, so a serving loop can do this); per-kernel events are then taken from the warm-up")
     ap.add_argument("--two-calls", action="store_true",
                     help="run flowmm_plan then flowmm_merge instead of the one-call flowmm_plan_merge")
     ap.add_argument("--flow-exact", action="store_true",
@@ -219,6 +222,7 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
 
     def step():
+        nonlocal stream
         if args.two_calls:
             bufs.plan(K, Q, stream)
             bufs.merge(K, V, stream)
@@ -244,17 +248,39 @@ def main():
     kernels_us = {k: 1e3 * ms / n for k, (ms, n) in per_kernel.items()}
     dominant = args.kernel or max(kernels_us, key=kernels_us.get)
 
-    # timed region: exactly K steps; only the dominant kernel carries events
-    fb.flowmm_profile_select(dominant)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    t_host = time.perf_counter() - t0
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    dom_ms, dom_n = fb.flowmm_profile_collect()[dominant]
-    fb.flowmm_profile_select("")
+    if args.graph:
+        # the dominant kernel's duration comes from eager steps (events cannot be recorded inside the graph)
+        fb.flowmm_profile_select(dominant)
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        dom_ms, dom_n = fb.flowmm_profile_collect()[dominant]
+        fb.flowmm_profile_select("")
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            stream = torch.cuda.current_stream().cuda_stream
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        t_host = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        # timed region: exactly K steps; only the dominant kernel carries events
+        fb.flowmm_profile_select(dominant)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        t_host = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        dom_ms, dom_n = fb.flowmm_profile_collect()[dominant]
+        fb.flowmm_profile_select("")
 
     ms_per_step = 1e3 * (t1 - t0) / args.steps
     tokens_per_s = wl.total_tokens / (ms_per_step * 1e-3)
@@ -270,6 +296,7 @@ def main():
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "seqlens": wl.seqlens, "budgets": wl.budgets,
                    "window": wl.window, "theta": wl.theta, "tokens_per_step": wl.total_tokens,
                    "entry_point": "flowmm_plan + flowmm_merge" if args.two_calls else "flowmm_plan_merge",
+                   "hip_graph_replay": bool(args.graph),
                    "token_layer_kvheads_per_s": tokens_per_s * wl.n_layers * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
