@@ -225,6 +225,47 @@ def test_decode_attention_over_the_compacted_cache(oracle, name):
     print(f"max abs error {worst:.2e}", flush=True)
 
 
+def _random_case(rng, i):
+    """A seeded random small shape: lengths, spans, window, budgets, head grouping, dtype, path and flags."""
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.integers(1, 3))
+    G = int(rng.choice([1, 1, 2, 3])) if dtype == "bf16" else int(rng.choice([1, 2]))
+    batch = int(rng.choice([1, 1, 1, 2, 3]))
+    W = int(rng.integers(1, 41))
+    spans, budgets = [], []
+    for _ in range(batch):
+        n_spans = int(rng.integers(1, 6))
+        lens = [int(rng.integers(1, 260)) for _ in range(n_spans)]
+        L = sum(lens)
+        if L < W:
+            lens[-1] += W - L
+            L = W
+        spans.append(tuple(lens))
+        budgets.append(int(rng.integers(W, L + 1)))
+    flags = int(rng.choice([0, 0, 2, 4, 6]))
+    path = str(rng.choice(["auto", "generic", "fused"]))
+    theta = float(rng.choice([0.25, 0.25, -1.0, 2.0]))
+    tau_factor = float(rng.choice([4.0, 4.0, 1.0, float("inf")]))
+    w = wl.make_workload(f"random{i}", dtype, 1000 + i, int(rng.integers(1, 3)), Hkv * G, Hkv, d, W,
+                         [list(sp) for sp in spans], [10] * batch, theta=theta, tau_factor=tau_factor, budgets=budgets,
+                         first_mod=int(rng.integers(0, 2)))
+    return w, flags, path
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_shapes_match_oracle(oracle, block):
+    """Forty seeded random shapes (ten per block) through a random path and random variant flags."""
+    rng = np.random.default_rng(2511_05534 + block)
+    for i in range(10):
+        w, flags, path = _random_case(rng, 10 * block + i)
+        print(f"random case {10 * block + i} [{path}, flags={flags}]: L={w.seqlens} B={w.budgets} W={w.window} "
+              f"Hq={w.n_q_heads} Hkv={w.n_kv_heads} d={w.head_dim} {w.dtype} theta={w.theta}", flush=True)
+        gpu = run_gpu(w, flags=flags | (1 if path == "generic" else 0), fused=path == "fused")
+        for l in range(w.n_layers):
+            check_layer(oracle, w, gpu, l, flags=flags)
+
+
 def test_hip_graph_replay_equals_eager():
     """The library neither allocates nor synchronises, so its calls can be captured into a HIP graph:
     every replay (with eager work and synchronisation in between) must reproduce the eager result."""
