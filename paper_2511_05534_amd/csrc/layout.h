@@ -40,9 +40,11 @@ enum SeqWord {
 };
 
 // tiling constants shared by host sizing and kernels
-constexpr int kScoreWaves = 4;
+// Eight waves with few registers each: two such workgroups fit a compute unit, so that one computes
+// with two waves per SIMD (matrix and vector phases overlap) while the other waits for its keys.
+constexpr int kScoreWaves = 8;
 // 32-key groups a wave of the score kernels holds in registers (its MFMA operands)
-constexpr int score_subs(bool bf16) { return bf16 ? 4 : 2; }
+constexpr int score_subs(bool bf16) { return bf16 ? 2 : 1; }
 constexpr int score_tile_keys(bool bf16) { return kScoreWaves * 32 * score_subs(bf16); }  // keys per workgroup
 constexpr int kMatchWaves = 4;
 // 32-token groups a wave of the match kernel holds in registers (its MFMA B operands)

@@ -40,6 +40,24 @@ __device__ __forceinline__ void load_to_lds(const void *gptr, void *lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
 }
 
+// sum of squares of a chunk added to s; bf16 pairs go through the two-element dot product instruction
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+template <bool BF16>
+__device__ __forceinline__ float chunk_sumsq_acc(const uint4 &c, float s) {
+  if constexpr (BF16) {
+    const unsigned w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x2_t v;
+      __builtin_memcpy(&v, &w[j], 4);
+      s = __builtin_amdgcn_fdot2_f32_bf16(v, v, s, false);
+    }
+    return s;
+  } else {
+    return s + chunk_sumsq<false>(c);
+  }
+}
+
 template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
   using CF = Cfg<BF16, D>;
@@ -52,6 +70,7 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
   constexpr int RS = NCH + 1;  // row stride in chunks: the odd stride keeps 16 rows' fragments on distinct banks
   uint4 *lds_rows = lds;                                             // [2][ROWS][RS]
   float *lds_w = reinterpret_cast<float *>(lds + 2 * ROWS * RS);     // [2][ROWS]
+  int *lds_tok = reinterpret_cast<int *>(lds_w + 2 * ROWS);          // [TILE] tokens to assign, or -1
 
   const Shape &sh = c.sh;
   const int *meta = c.meta;
@@ -116,17 +135,29 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
     const int vc = min(wv0 + sub * 32 + n, cn - 1);
     return cross ? vc : order[vc];
   };
+  // Whether a token still waits for a pivot is asked for now, next to the key loads, and kept in
+  // LDS: the end of the kernel then has one dependent load (the slot of the winning list entry) left.
+  int tok[KS], state[KS];
 #pragma unroll
   for (int sub = 0; sub < KS; ++sub) {
-    const uint4 *row = K + (long long)token_of(sub) * sh.ks_tok + half;
+    tok[sub] = token_of(sub);
+    state[sub] = assign[tok[sub]];
+  }
+#pragma unroll
+  for (int sub = 0; sub < KS; ++sub) {
+    const uint4 *row = K + (long long)tok[sub] * sh.ks_tok + half;
 #pragma unroll
     for (int f = 0; f < NF; ++f) kf[sub][f] = row[2 * f];
   }
 #pragma unroll
+  for (int sub = 0; sub < KS; ++sub)
+    if (half == 0)
+      lds_tok[wave * 32 * KS + sub * 32 + n] = (wv0 + sub * 32 + n < cn && state[sub] == -2) ? tok[sub] : -1;
+#pragma unroll
   for (int sub = 0; sub < KS; ++sub) {
     float ss = 0.f;
 #pragma unroll
-    for (int f = 0; f < NF; ++f) ss += chunk_sumsq<BF16>(kf[sub][f]);
+    for (int f = 0; f < NF; ++f) ss = chunk_sumsq_acc<BF16>(kf[sub][f], ss);
     ss += __shfl_xor(ss, 32, 64);
     shift[sub] = sqrtf(ss) * 1.001f;  // >= |<token, pivot>| / |pivot| for every pivot
   }
@@ -208,10 +239,10 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
     const unsigned other = __shfl_xor(best[sub], 32, 64) >> 4;
     const int oe = __shfl_xor(e, 32, 64);
     if (other > mine || (other == mine && oe < e)) e = oe;
-    const int tok = token_of(sub);
-    if (half == 0 && wv0 + sub * 32 + n < cn && assign[tok] == -2) {
+    const int tk = half == 0 ? lds_tok[wave * 32 * KS + sub * 32 + n] : -1;  // written by this very lane
+    if (tk >= 0) {
       const int slot = npc > 0 ? pl_slot[e] : -1;
-      assign[tok] = slot;
+      assign[tk] = slot;
       dropped += slot < 0;
     }
   }
@@ -224,7 +255,8 @@ hipError_t launch_match_t(const Ctx &c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   constexpr int ROWS = match_tile_rows(NCH);
   const Shape &sh = c.sh;
-  const size_t lds = 2 * (size_t)ROWS * (NCH + 1) * 16 + 2 * ROWS * sizeof(float);
+  const size_t lds = 2 * (size_t)ROWS * (NCH + 1) * 16 + 2 * ROWS * sizeof(float) +
+                     (size_t)match_tile_tokens(BF16) * sizeof(int);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(match_kernel<BF16, D>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

@@ -16,6 +16,7 @@
 #include "kernels.h"
 #include "profile.h"
 #include "score_core.h"
+#include "trace.h"
 
 namespace flowmm {
 
@@ -63,19 +64,26 @@ template <bool BF16, int D>
 __device__ __forceinline__ void stage_queries(const Ctx &c, const TileCtx &t, uint4 *ldsq) {
   constexpr int NCH = Cfg<BF16, D>::NCH, RS = NCH + 1;
   const Shape &sh = c.sh;
-  const uint4 *Q = reinterpret_cast<const uint4 *>(c.Q) + (long long)t.l * sh.qs_layer;
+  const uint4 *Q = reinterpret_cast<const uint4 *>(c.Q) + (long long)t.l * sh.qs_layer +
+                   (long long)(t.gkv * sh.G) * sh.qs_head + (long long)(t.b * sh.W) * sh.qs_tok;
   const uint4 *zero = reinterpret_cast<const uint4 *>(c.meta + MW_ZERO16);
   const int total = sh.R_pad * RS;
+  // chunk q of the LDS image is chunk ch of row r of head g; q advances by the workgroup size per
+  // trip, so (g, r, ch) are carried along instead of being divided out again
+  constexpr int kRowStep = kThreads / RS, kChStep = kThreads % RS;
+  int q = t.wave * 64 + t.lane;
+  int row = q / RS, ch = q - row * RS;
+  int g = row / sh.W_pad, r = row - g * sh.W_pad;
   for (int q0 = t.wave * 64; q0 < total; q0 += kThreads) {
-    const int q = q0 + t.lane;
-    if (q < total) {
-      const int row = q / RS, ch = q - row * RS;
-      const int g = row / sh.W_pad, r = row - g * sh.W_pad;
+    if (q0 + t.lane < total) {
       const uint4 *src = zero;
-      if (r < sh.W && ch < NCH)
-        src = Q + (long long)(t.gkv * sh.G + g) * sh.qs_head + (long long)(t.b * sh.W + r) * sh.qs_tok + ch;
+      if (r < sh.W && ch < NCH) src = Q + (long long)g * sh.qs_head + (long long)r * sh.qs_tok + ch;
       load16_to_lds(src, ldsq + q0);
     }
+    ch += kChStep;
+    r += kRowStep;
+    if (ch >= RS) { ch -= RS; ++r; }
+    while (r >= sh.W_pad) { r -= sh.W_pad; ++g; }
   }
 }
 
@@ -98,9 +106,9 @@ __device__ __forceinline__ void load_keys(const Ctx &c, const TileCtx &t, uint4 
 // ---- pass 1: per-tile row statistics ---------------------------------------------------
 template <bool BF16, int D, int KS, bool MASKED>
 __device__ __forceinline__ void stats_body(const Ctx &c, const TileCtx &t, const uint4 (&kf)[KS][Cfg<BF16, D>::NF],
-                                           const uint4 *ldsq, float2 *lds_stats) {
+                                           const uint4 *ldsq, float *lds_stats) {
   constexpr int NF = Cfg<BF16, D>::NF, RS = Cfg<BF16, D>::NCH + 1;
-  constexpr int AHEAD = NF < 3 ? NF : 3;
+  constexpr int AHEAD = NF < 2 ? NF : 2;
   const Shape &sh = c.sh;
   const int RB = sh.R_pad >> 5;
   const float cl = sh.scale_log2e;
@@ -145,42 +153,49 @@ __device__ __forceinline__ void stats_body(const Ctx &c, const TileCtx &t, const
     }
     const float m2 = __shfl_xor(m, 32, 64), z2 = __shfl_xor(z, 32, 64);
     stat_combine(m, z, m2, z2);
-    if (t.half == 0) lds_stats[t.wave * sh.R_pad + row] = make_float2(m, z);
+    // log2 of the row's sum of 2^logit over this wave's keys: the pair (that, 1) stands for (m, z)
+    if (t.half == 0) lds_stats[t.wave * sh.R_pad + row] = m + __builtin_amdgcn_logf(z);
   }
 }
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads, 2) void score_stats_kernel(Ctx c) {
+__global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF, KS = score_subs(BF16);
   extern __shared__ uint4 lds[];
   const Shape &sh = c.sh;
   TileCtx t;
+  TRACE(0);
   if (!tile_ctx<score_tile_keys(BF16)>(c, t)) return;
   uint4 *ldsq = lds;
-  float2 *lds_stats = reinterpret_cast<float2 *>(lds + sh.R_pad * (NCH + 1));  // [waves][R_pad]
-
-  stage_queries<BF16, D>(c, t, ldsq);
+  float *lds_stats = reinterpret_cast<float *>(lds + sh.R_pad * (NCH + 1));  // [waves][R_pad]
+  TRACE(1);
   uint4 kf[KS][NF];
-  load_keys<BF16, D, KS>(c, t, kf);
+  load_keys<BF16, D, KS>(c, t, kf);  // the long way first (HBM); the query rows come from L2
+  TRACE(2);
+  stage_queries<BF16, D>(c, t, ldsq);
+  TRACE(3);
   __builtin_amdgcn_s_waitcnt(0);
+  TRACE(4);
   __syncthreads();
+  TRACE(5);
   if (t.key0 < t.s.L) {  // waves past the end of the sequence have nothing to add
     if (t.masked) stats_body<BF16, D, KS, true>(c, t, kf, ldsq, lds_stats);
     else stats_body<BF16, D, KS, false>(c, t, kf, ldsq, lds_stats);
   } else {
-    for (int row = t.lane; row < sh.R_pad; row += 64) lds_stats[t.wave * sh.R_pad + row] = make_float2(-INFINITY, 0.f);
+    for (int row = t.lane; row < sh.R_pad; row += 64) lds_stats[t.wave * sh.R_pad + row] = -INFINITY;
   }
+  TRACE(6);
   __syncthreads();
+  TRACE(7);
   float2 *out = c.part_stats + ((long long)(t.l * sh.Hkv + t.gkv) * sh.tiles_score + t.x) * sh.R_pad;
   for (int row = threadIdx.x; row < sh.R_pad; row += kThreads) {
-    float2 a = lds_stats[row];
+    float2 a = make_float2(lds_stats[row], 1.f);
+    if (a.x == -INFINITY) a.y = 0.f;
 #pragma unroll
-    for (int w = 1; w < kScoreWaves; ++w) {
-      const float2 o = lds_stats[w * sh.R_pad + row];
-      stat_combine(a.x, a.y, o.x, o.y);
-    }
+    for (int w = 1; w < kScoreWaves; ++w) stat_combine(a.x, a.y, lds_stats[w * sh.R_pad + row], 1.f);
     out[row] = a;
   }
+  TRACE(8);
 }
 
 // ---- pass 2: fold the tiles of a sequence ----------------------------------------------
@@ -210,7 +225,7 @@ __device__ __forceinline__ void colsum_body(const Ctx &c, const TileCtx &t, cons
                                             const int (&keymod)[KS], const uint4 *ldsq, const float *lds_c,
                                             const float *lds_rowimg, float *lds_cross, float (&colsum)[KS]) {
   constexpr int NF = Cfg<BF16, D>::NF, RS = Cfg<BF16, D>::NCH + 1;
-  constexpr int AHEAD = NF < 3 ? NF : 3;
+  constexpr int AHEAD = 1;  // registers are short here: one fragment in flight
   const Shape &sh = c.sh;
   const int RB = sh.R_pad >> 5;
   const int bph = sh.W_pad >> 5;  // row blocks per query head
@@ -224,35 +239,42 @@ __device__ __forceinline__ void colsum_body(const Ctx &c, const TileCtx &t, cons
   for (int rb = 0; rb < RB; ++rb) {
     f32x16_t acc[KS];
     block_products<BF16, D, KS, false, AHEAD>(acc, kf, pf, qbase + rb * (32 * RS * 16), rb + 1 < RB);  // [query row][key]
-    float cr[16], wimg[16];
+    float bs[KS], bsi[KS];
+#pragma unroll
+    for (int sub = 0; sub < KS; ++sub) bs[sub] = bsi[sub] = 0.f;
+    // rows 8g + 4 half + j of the block, j = 0..3 (the fences keep the compiler from fetching the
+    // constants of all four groups up front: registers are short)
+    const float *crow = lds_c + rb * 32 + 4 * t.half, *wrow = lds_rowimg + rbh * 32 + 4 * t.half;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const float4 c4 = *reinterpret_cast<const float4 *>(lds_c + rb * 32 + 8 * g + 4 * t.half);
-      cr[4 * g] = c4.x; cr[4 * g + 1] = c4.y; cr[4 * g + 2] = c4.z; cr[4 * g + 3] = c4.w;
-      if constexpr (WIN_IMG) {
-        const float4 w4 = *reinterpret_cast<const float4 *>(lds_rowimg + rbh * 32 + 8 * g + 4 * t.half);
-        wimg[4 * g] = w4.x; wimg[4 * g + 1] = w4.y; wimg[4 * g + 2] = w4.z; wimg[4 * g + 3] = w4.w;
+      const float4 c4 = *reinterpret_cast<const float4 *>(crow + 8 * g);
+      float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if constexpr (WIN_IMG) w4 = *reinterpret_cast<const float4 *>(wrow + 8 * g);
+      const float cr[4] = {c4.x, c4.y, c4.z, c4.w};
+      const float wimg[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+      for (int sub = 0; sub < KS; ++sub) {
+        const int key = t.key0 + sub * 32 + t.n;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float p = fast_exp2(fmaf(acc[sub][4 * g + j], cl, -cr[j]));
+          if constexpr (MASKED) {
+            // window row r sees keys up to L - W + r; padding rows already have probability 0
+            const int r = rbh * 32 + 8 * g + 4 * t.half + j;
+            p = key <= t.s.L - sh.W + r ? p : 0.f;
+          }
+          bs[sub] += p;
+          if constexpr (WIN_IMG) bsi[sub] = fmaf(p, wimg[j], bsi[sub]);
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int sub = 0; sub < KS; ++sub) {
-      const int key = t.key0 + sub * 32 + t.n;
-      float bs = 0.f, bsi = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float p = fast_exp2(fmaf(acc[sub][i], cl, -cr[i]));
-        if constexpr (MASKED) {
-          // window row r sees keys up to L - W + r; padding rows already have probability 0
-          const int r = rbh * 32 + acc_row(i, t.half);
-          p = key <= t.s.L - sh.W + r ? p : 0.f;
-        }
-        bs += p;
-        if constexpr (WIN_IMG) bsi = fmaf(p, wimg[i], bsi);
-      }
-      colsum[sub] += bs;
+      colsum[sub] += bs[sub];
       // mass sent to the other modality: image keys seen by text rows, text keys by image rows
-      if constexpr (WIN_IMG) cross_acc += keymod[sub] ? bs - bsi : bsi;
-      else cross_acc += keymod[sub] ? bs : 0.f;
+      if constexpr (WIN_IMG) cross_acc += keymod[sub] ? bs[sub] - bsi[sub] : bsi[sub];
+      else cross_acc += keymod[sub] ? bs[sub] : 0.f;
     }
     if (++rbh == bph) {
       rbh = 0;
@@ -264,7 +286,7 @@ __device__ __forceinline__ void colsum_body(const Ctx &c, const TileCtx &t, cons
 }
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads, 2) void score_colsum_kernel(Ctx c) {
+__global__ __launch_bounds__(kThreads, 4) void score_colsum_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF, KS = score_subs(BF16);
   extern __shared__ uint4 lds[];
   const Shape &sh = c.sh;
@@ -275,9 +297,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_colsum_kernel(Ctx c) {
   float *lds_rowimg = lds_c + sh.R_pad;                                  // [W_pad]
   float *lds_cross = lds_rowimg + sh.W_pad;                              // [waves][G]
 
-  stage_queries<BF16, D>(c, t, ldsq);
   uint4 kf[KS][NF];
-  load_keys<BF16, D, KS>(c, t, kf);
+  load_keys<BF16, D, KS>(c, t, kf);  // the long way first (HBM); the query rows come from L2
+  stage_queries<BF16, D>(c, t, ldsq);
   const float *rs = c.rowstat + ((long long)(t.l * sh.Hkv + t.gkv) * sh.batch + t.b) * sh.R_pad;
   for (int row = threadIdx.x; row < sh.R_pad; row += kThreads) lds_c[row] = rs[row];
   const uint8_t *mod = c.mod + t.s.tok_off;
@@ -328,7 +350,7 @@ hipError_t launch_score_t(const Ctx &c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   const Shape &sh = c.sh;
   const size_t q_bytes = (size_t)sh.R_pad * (NCH + 1) * 16;
-  const size_t lds1 = q_bytes + (size_t)kScoreWaves * sh.R_pad * sizeof(float2);
+  const size_t lds1 = q_bytes + (size_t)kScoreWaves * sh.R_pad * sizeof(float);
   const size_t lds3 = q_bytes + (size_t)sh.R_pad * 4 + (size_t)sh.W_pad * 4 + (size_t)kScoreWaves * sh.G * 4;
   hipError_t e;
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_stats_kernel<BF16, D>),
@@ -357,9 +379,17 @@ hipError_t launch_score_t(const Ctx &c) {
 
 }  // namespace
 
+#ifdef FLOWMM_TRACE
+}  // namespace flowmm
+extern "C" __attribute__((visibility("default"))) int flowmm_trace_set_score(void *p) {
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(flowmm::g_trace), &p, sizeof(p));
+}
+namespace flowmm {
+#endif
+
 size_t score_lds_bytes(const Shape &sh) {
   const int nch = sh.d * (sh.bf16 ? 2 : 4) / 16;
-  return (size_t)sh.R_pad * (nch + 1) * 16 + (size_t)kScoreWaves * sh.R_pad * sizeof(float2) +
+  return (size_t)sh.R_pad * (nch + 1) * 16 + (size_t)kScoreWaves * sh.R_pad * sizeof(float) +
          (size_t)sh.W_pad * 4 + (size_t)kScoreWaves * sh.G * 4;
 }
 
