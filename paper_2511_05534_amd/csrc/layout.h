@@ -46,9 +46,10 @@ constexpr int kScoreWaves = 8;
 // 32-key groups a wave of the score kernels holds in registers (its MFMA operands)
 constexpr int score_subs(bool bf16) { return bf16 ? 2 : 1; }
 constexpr int score_tile_keys(bool bf16) { return kScoreWaves * 32 * score_subs(bf16); }  // keys per workgroup
-constexpr int kMatchWaves = 4;
+// As in the score kernels: eight waves with few registers, two workgroups per compute unit
+constexpr int kMatchWaves = 8;
 // 32-token groups a wave of the match kernel holds in registers (its MFMA B operands)
-constexpr int match_subs(bool bf16) { return bf16 ? 4 : 2; }
+constexpr int match_subs(bool bf16) { return bf16 ? 2 : 1; }
 constexpr int match_tile_tokens(bool bf16) { return kMatchWaves * 32 * match_subs(bf16); }  // tokens per workgroup
 // packed pivot rows staged in LDS at a time: 32 KB worth, 128 rows at most (nch = 16-byte chunks per row)
 constexpr int match_tile_rows(int nch) { return 2048 / nch < 128 ? 2048 / nch : 128; }

@@ -59,7 +59,7 @@ __device__ __forceinline__ float chunk_sumsq_acc(const uint4 &c, float s) {
 }
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
+__global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
   using CF = Cfg<BF16, D>;
   constexpr int NCH = CF::NCH, NF = CF::NF;
   constexpr int KS = match_subs(BF16);
@@ -207,23 +207,31 @@ __global__ __launch_bounds__(kThreads, 2) void match_kernel(Ctx c) {
           for (int f = 0; f < kAhead; ++f)
             pf[f] = *reinterpret_cast<const uint4 *>(brow + kBlockBytes + 32 * f);
         }
-        float wv[16];  // 1/norm of this lane's 16 rows of the block
+        const int blk = t * NBLK + pb;
+        unsigned m[KS];
+#pragma unroll
+        for (int sub = 0; sub < KS; ++sub) m[sub] = 0u;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+          // 1/norm of rows 8g + 4 half + j of the block, j = 0..3 (the fence keeps the compiler from
+          // fetching all four groups up front: registers are short)
           const float4 w4 = *reinterpret_cast<const float4 *>(wt + pb * 128 + 32 * g);
-          wv[4 * g] = w4.x; wv[4 * g + 1] = w4.y; wv[4 * g + 2] = w4.z; wv[4 * g + 3] = w4.w;
+          const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+          for (int sub = 0; sub < KS; ++sub) {
+#pragma unroll
+            for (int j = 0; j < 4; j += 2) {
+              const int i = 4 * g + j;
+              const unsigned p0 = (__float_as_uint(fmaf(acc[sub][i], wv[j], shift[sub])) & ~15u) | (unsigned)(15 - i);
+              const unsigned p1 = (__float_as_uint(fmaf(acc[sub][i + 1], wv[j + 1], shift[sub])) & ~15u) | (unsigned)(14 - i);
+              m[sub] = max(max(m[sub], p0), p1);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        const int blk = t * NBLK + pb;
 #pragma unroll
         for (int sub = 0; sub < KS; ++sub) {
-          unsigned m = 0u;
-#pragma unroll
-          for (int i = 0; i < 16; i += 2) {
-            const unsigned p0 = (__float_as_uint(fmaf(acc[sub][i], wv[i], shift[sub])) & ~15u) | (unsigned)(15 - i);
-            const unsigned p1 = (__float_as_uint(fmaf(acc[sub][i + 1], wv[i + 1], shift[sub])) & ~15u) | (unsigned)(14 - i);
-            m = max(max(m, p0), p1);
-          }
-          if (m > best[sub]) { best[sub] = m; bblk[sub] = blk; }
+          if (m[sub] > best[sub]) { best[sub] = m[sub]; bblk[sub] = blk; }
         }
       }
     }
