@@ -216,7 +216,7 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   rg.seg_off = off; off += align256((size_t)units * (sumB + batch) * 4);
   rg.members = off; off += align256((size_t)units * T * 4);
   rg.tasks = off; off += align256((size_t)units * sh.tasks_total * sizeof(int4));
-  rg.n_tasks = off; off += align256((size_t)units * batch * 4);
+  rg.n_tasks = off; off += align256((size_t)units * batch * 2 * 4);
   rg.multi = off; off += align256((size_t)units * sh.multi_total * sizeof(int4));
   rg.n_multi = off; off += align256((size_t)units * batch * 4);
   rg.partials = off; off += align256((size_t)units * sh.part_total * 2 * sh.d * 4);

@@ -34,8 +34,9 @@ struct Ctx {
   uint4 *pack;         // [Lyr][Hkv][2*SBP][row chunks+1] their K rows, one chunk of padding after each
   int *seg_off;        // [Lyr][Hkv][SB + batch]          CSR offsets of the members of each slot
   int *members;        // [Lyr][Hkv][T]                   evicted tokens grouped by slot, ascending
-  int4 *tasks;         // [Lyr][Hkv][tasks_total]         (slot, first member, count, partial index or -1)
-  int *n_tasks;        // [Lyr][Hkv][batch]
+  int4 *tasks;         // [Lyr][Hkv][tasks_total]         (slot, first member, count, partial index or -1); per sequence the
+                       //                                 small ones from the front of its range, the others from the back
+  int *n_tasks;        // [Lyr][Hkv][batch][2]            how many of either kind
   int4 *multi;         // [Lyr][Hkv][multi_total]         (slot, first partial, number of partials, members)
   int *n_multi;        // [Lyr][Hkv][batch]
   float *partials;     // [Lyr][Hkv][part_total][2][d]    fp32 partial row sums of K and V

@@ -23,24 +23,28 @@ namespace flowmm {
 namespace {
 
 constexpr int kCsrThreads = kCsrWaves * 64;
+constexpr int kSmallTask = 4;  // a slot with fewer members is merged by one row group (pivot + members = loads in flight)
 
-__device__ __forceinline__ int block_exclusive_scan_1024(int v, int *lds_wave, int *total) {
+// Exclusive scan over the workgroup of a 64-bit value that packs several small counters (their
+// sums must not carry into each other); *total gets the sum over all threads.
+__device__ __forceinline__ unsigned long long block_exclusive_scan_packed(unsigned long long v, unsigned long long *lds_wave,
+                                                                      unsigned long long *total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
+  unsigned long long inc = v;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const int u = __shfl_up(inc, o, 64);
+    const unsigned long long u = __shfl_up(inc, o, 64);
     if (lane >= o) inc += u;
   }
   __syncthreads();
   if (lane == 63) lds_wave[wave] = inc;
   __syncthreads();
   if (wave == 0) {
-    const int w = lane < kCsrWaves ? lds_wave[lane] : 0;
-    int winc = w;
+    const unsigned long long w = lane < kCsrWaves ? lds_wave[lane] : 0ull;
+    unsigned long long winc = w;
 #pragma unroll
     for (int o = 1; o < kCsrWaves; o <<= 1) {
-      const int u = __shfl_up(winc, o, 64);
+      const unsigned long long u = __shfl_up(winc, o, 64);
       if (lane >= o) winc += u;
     }
     if (lane < kCsrWaves) lds_wave[lane] = winc - w;
@@ -62,9 +66,10 @@ __device__ __forceinline__ unsigned long long same_slot_mask(bool member, int sl
   return m;
 }
 
-__global__ __launch_bounds__(kCsrThreads) void merge_csr_kernel(Ctx c, int nw_shift) {
+// at most 64 registers: two workgroups of 16 waves then share a compute unit
+__global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw_shift) {
   extern __shared__ int lds_tbl[];  // [B][NW] per-wave counts, later write cursors
-  __shared__ int lds_wave[kCsrWaves + 1];
+  __shared__ unsigned long long lds_wave[kCsrWaves + 1];
   const Shape &sh = c.sh;
   const int *meta = c.meta;
   const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
@@ -77,6 +82,7 @@ __global__ __launch_bounds__(kCsrThreads) void merge_csr_kernel(Ctx c, int nw_sh
   int *members = c.members + unit * sh.T + s.tok_off;
   int *seg_off = c.seg_off + unit * (sh.SB + sh.batch) + s.kept_off + b;
   const int task_base = (meta + meta[MW_OFF_CU_TASK])[b];
+  const int task_room = (meta + meta[MW_OFF_CU_TASK])[b + 1] - task_base;
   const int multi_base = (meta + meta[MW_OFF_CU_MULTI])[b];
   const int part_base = (meta + meta[MW_OFF_CU_PART])[b];
   int4 *tasks = c.tasks + unit * sh.tasks_total + task_base;
@@ -103,7 +109,9 @@ __global__ __launch_bounds__(kCsrThreads) void merge_csr_kernel(Ctx c, int nw_sh
   __syncthreads();
 
   // scan over slots: segment offsets, write cursors, task list
-  int seg_carry = 0, task_carry = 0, multi_carry = 0, part_carry = 0;
+  // A slot with fewer than kSmallTask members is a small task (a row group of the task kernel does it
+  // alone); the small tasks fill the sequence's range of the table from the front, the others from the back.
+  int seg_carry = 0, small_carry = 0, task_carry = 0, multi_carry = 0, part_carry = 0;
   for (int s0 = 0; s0 < s.B; s0 += kCsrThreads) {
     const int slot = s0 + threadIdx.x;
     int n = 0;
@@ -111,11 +119,18 @@ __global__ __launch_bounds__(kCsrThreads) void merge_csr_kernel(Ctx c, int nw_sh
       for (int w = 0; w < NW; ++w) n += lds_tbl[slot * NW + w];
     const int nt = slot < s.B ? max(1, (n + kTaskChunk - 1) / kTaskChunk) : 0;
     const int is_multi = nt > 1;
-    int tot_n, tot_t, tot_m, tot_p;
-    const int seg = seg_carry + block_exclusive_scan_1024(n, lds_wave, &tot_n);
-    const int tb = task_carry + block_exclusive_scan_1024(nt, lds_wave, &tot_t);
-    const int mb = multi_carry + block_exclusive_scan_1024(is_multi, lds_wave, &tot_m);
-    const int pb = part_carry + block_exclusive_scan_1024(is_multi ? nt : 0, lds_wave, &tot_p);
+    const int is_small = slot < s.B && n < kSmallTask;
+    // two scans of packed counters: (members, small tasks) and (other tasks, partials, split slots), 21 bits each
+    constexpr unsigned long long kF = (1ull << 21) - 1;
+    unsigned long long tot_a, tot_b;
+    const unsigned long long ea = block_exclusive_scan_packed((unsigned long long)n | ((unsigned long long)is_small << 32), lds_wave, &tot_a);
+    const unsigned long long eb = block_exclusive_scan_packed(
+        (unsigned long long)(is_small ? 0 : nt) | ((unsigned long long)(is_multi ? nt : 0) << 21) | ((unsigned long long)is_multi << 42),
+        lds_wave, &tot_b);
+    const int seg = seg_carry + (int)(ea & 0xffffffffull), sb = small_carry + (int)(ea >> 32);
+    const int tb = task_carry + (int)(eb & kF), pb = part_carry + (int)((eb >> 21) & kF), mb = multi_carry + (int)(eb >> 42);
+    const int tot_n = (int)(tot_a & 0xffffffffull), tot_s = (int)(tot_a >> 32);
+    const int tot_t = (int)(tot_b & kF), tot_p = (int)((tot_b >> 21) & kF), tot_m = (int)(tot_b >> 42);
     if (slot < s.B) {
       seg_off[slot] = seg;
       int base = seg;
@@ -124,19 +139,23 @@ __global__ __launch_bounds__(kCsrThreads) void merge_csr_kernel(Ctx c, int nw_sh
         lds_tbl[slot * NW + w] = base;
         base += t;
       }
-      for (int j = 0; j < nt; ++j)
-        tasks[tb + j] = make_int4(slot, seg + j * kTaskChunk, min(kTaskChunk, n - j * kTaskChunk),
-                                  is_multi ? part_base + pb + j : -1);
+      if (is_small) tasks[sb] = make_int4(slot, seg, n, -1);
+      else
+        for (int j = 0; j < nt; ++j)
+          tasks[task_room - 1 - (tb + j)] = make_int4(slot, seg + j * kTaskChunk, min(kTaskChunk, n - j * kTaskChunk),
+                                                      is_multi ? part_base + pb + j : -1);
       if (is_multi) multi[mb] = make_int4(slot, part_base + pb, nt, n);
     }
     seg_carry += tot_n;
+    small_carry += tot_s;
     task_carry += tot_t;
     multi_carry += tot_m;
     part_carry += tot_p;
   }
   if (threadIdx.x == 0) {
     seg_off[s.B] = seg_carry;
-    c.n_tasks[unit * sh.batch + b] = task_carry;
+    c.n_tasks[(unit * sh.batch + b) * 2] = small_carry;
+    c.n_tasks[(unit * sh.batch + b) * 2 + 1] = task_carry;
     c.n_multi[unit * sh.batch + b] = multi_carry;
   }
   __syncthreads();
@@ -164,60 +183,47 @@ template <bool BF16, int D, bool WEIGHTED>
 __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
   using CF = Cfg<BF16, D>;
   constexpr int LPR = CF::NCH;        // lanes that cover one row
-  constexpr int RPL = 64 / LPR;       // rows a wave covers per load
+  constexpr int RPL = 64 / LPR;       // rows a wave covers per load = row groups of a wave
   constexpr int EPC = CF::kElemsPerChunk;
   constexpr int U = 4;                // loads in flight per lane and tensor
   const Shape &sh = c.sh;
   const int *meta = c.meta;
   const int *cu = meta + meta[MW_OFF_CU_TASK];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int q = blockIdx.x * 4 + wave;
-  if (q >= sh.tasks_total) return;
+  // One wave per entry of the task table.  Most slots have a few members or none: RPL such small
+  // tasks (whole slot, at most U - 1 members) are done side by side by the row groups of a wave,
+  // so the waves at the front of a sequence's range take RPL of them each; the waves at the back of
+  // the range stream one larger task each; those in between have nothing to do.
+  static_assert(U == kSmallTask, "a small task is the pivot and fewer than U members");
+  const int w = blockIdx.x * 4 + wave;
+  if (w >= sh.tasks_total) return;
   const int gkv = blockIdx.y, l = blockIdx.z;
   const long long unit = (long long)l * sh.Hkv + gkv;
-  const int b = find_seq(cu, meta[MW_BATCH], q);
-  const int ql = q - cu[b];
-  if (ql >= c.n_tasks[unit * sh.batch + b]) return;
+  const int b = find_seq(cu, meta[MW_BATCH], w);
+  const int wl = w - cu[b], room = cu[b + 1] - cu[b];
+  const int n_small = c.n_tasks[(unit * sh.batch + b) * 2], n_big = c.n_tasks[(unit * sh.batch + b) * 2 + 1];
+  const bool small_wave = wl * RPL < n_small;
+  if (!small_wave && wl < room - n_big) return;
   const SeqInfo s = load_seq(meta, b);
-  const int4 task = c.tasks[unit * sh.tasks_total + q];  // (slot, first member, count, partial index)
   const int rg = lane / LPR, ch = lane % LPR;
   const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + head_off;
   const uint4 *V = reinterpret_cast<const uint4 *>(c.V) + head_off;
-  const int *members = c.members + unit * sh.T + s.tok_off + task.y;
+  const int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
+  const int *seq_members = c.members + unit * sh.T + s.tok_off;
+  uint4 *K_out = reinterpret_cast<uint4 *>(c.K_out) + (unit * sh.SB + s.kept_off) * LPR;
+  uint4 *V_out = reinterpret_cast<uint4 *>(c.V_out) + (unit * sh.SB + s.kept_off) * LPR;
+  const int4 *seq_tasks = c.tasks + unit * sh.tasks_total + cu[b];
 
-  float ak[EPC], av[EPC];
-#pragma unroll
-  for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
-  const bool single = task.w < 0;
-  const int pivot_tok = c.kept_idx[unit * sh.SB + s.kept_off + task.x];
-  float wsum = 0.f;        // weighted merge: weights this row group has added
-  float pk[EPC], pss = 0.f;  // weighted merge: this lane's chunk of the pivot's key, its squared norm
-  if constexpr (WEIGHTED) {
-    chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], pk);
-#pragma unroll
-    for (int e = 0; e < EPC; ++e) pss = fmaf(pk[e], pk[e], pss);
-#pragma unroll
-    for (int o = LPR / 2; o >= 1; o >>= 1) pss += __shfl_xor(pss, o, 64);
-  }
-  if (single && rg == 0) {
-    if constexpr (WEIGHTED) {
-#pragma unroll
-      for (int e = 0; e < EPC; ++e) ak[e] = pk[e];
-      wsum = 1.f;
-    } else {
-      chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], ak);
-    }
-    chunk_to_floats<BF16>(V[(long long)pivot_tok * sh.ks_tok + ch], av);
-  }
-  for (int j0 = rg; j0 < task.z; j0 += RPL * U) {
+  // ---- small tasks: the pivot's row and up to U - 1 member rows, summed in that order by one row group
+  if (small_wave) {
+    if (wl * RPL + rg >= n_small) return;
+    const int4 mine = seq_tasks[wl * RPL + rg];  // (slot, first member, count, -1)
     int tokv[U];
-    uint4 kc[U], vc[U];
+    tokv[0] = kept[mine.x];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int j = j0 + u * RPL;
-      tokv[u] = j < task.z ? members[j] : -1;
-    }
+    for (int u = 1; u < U; ++u) tokv[u] = u <= mine.z ? seq_members[mine.y + u - 1] : -1;
+    uint4 kc[U], vc[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (tokv[u] >= 0) {
@@ -225,60 +231,155 @@ __global__ __launch_bounds__(256) void merge_tasks_kernel(Ctx c) {
         vc[u] = V[(long long)tokv[u] * sh.ks_tok + ch];
       }
     }
+    float ak[EPC], av[EPC];
+    chunk_to_floats<BF16>(kc[0], ak);
+    chunk_to_floats<BF16>(vc[0], av);
+    float den = (float)(1 + mine.z);
+    if constexpr (WEIGHTED) {
+      float pk[EPC], pss = 0.f;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      // every lane takes part in the exchanges below, so rows past the end count as zero rows
-      float fk[EPC], fv[EPC];
-      const bool real = tokv[u] >= 0;
-      if (real) {
-        chunk_to_floats<BF16>(kc[u], fk);
-        chunk_to_floats<BF16>(vc[u], fv);
-      } else {
+      for (int e = 0; e < EPC; ++e) { pk[e] = ak[e]; pss = fmaf(pk[e], pk[e], pss); }
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) fk[e] = fv[e] = 0.f;
-      }
-      if constexpr (WEIGHTED) {
+      for (int o = LPR / 2; o >= 1; o >>= 1) pss += __shfl_xor(pss, o, 64);
+      den = 1.f;
+#pragma unroll
+      for (int u = 1; u < U; ++u) {
+        // lanes of other row groups may be elsewhere: the exchanges stay inside this row group
+        float fk[EPC], fv[EPC];
+        const bool real = tokv[u] >= 0;
+        if (real) {
+          chunk_to_floats<BF16>(kc[u], fk);
+          chunk_to_floats<BF16>(vc[u], fv);
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) fk[e] = fv[e] = 0.f;
+        }
         float dot = 0.f, ss = 0.f;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) { dot = fmaf(fk[e], pk[e], dot); ss = fmaf(fk[e], fk[e], ss); }
 #pragma unroll
         for (int o = LPR / 2; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o, 64); ss += __shfl_xor(ss, o, 64); }
         const float w = ss > 0.f && pss > 0.f ? fmaxf(dot / (sqrtf(ss) * sqrtf(pss)), 0.f) : 0.f;
-        wsum += w;
+        den += w;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) { ak[e] = fmaf(w, fk[e], ak[e]); av[e] = fmaf(w, fv[e], av[e]); }
-      } else if (real) {
+      }
+    } else {
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
+      for (int u = 1; u < U; ++u) {
+        if (tokv[u] >= 0) {
+          float fk[EPC], fv[EPC];
+          chunk_to_floats<BF16>(kc[u], fk);
+          chunk_to_floats<BF16>(vc[u], fv);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
+        }
       }
     }
-  }
-  // fold the row groups (fixed tree)
-#pragma unroll
-  for (int o = LPR; o < 64; o <<= 1) {
-#pragma unroll
-    for (int e = 0; e < EPC; ++e) {
-      ak[e] += __shfl_xor(ak[e], o, 64);
-      av[e] += __shfl_xor(av[e], o, 64);
-    }
-    if constexpr (WEIGHTED) wsum += __shfl_xor(wsum, o, 64);
-  }
-  if (rg != 0) return;
-  if (single) {
-    const float den = WEIGHTED ? wsum : (float)(1 + task.z);
 #pragma unroll
     for (int e = 0; e < EPC; ++e) { ak[e] = ak[e] / den; av[e] = av[e] / den; }
-    const long long orow = (unit * sh.SB + s.kept_off + task.x) * LPR + ch;
-    reinterpret_cast<uint4 *>(c.K_out)[orow] = floats_to_chunk<BF16>(ak);
-    reinterpret_cast<uint4 *>(c.V_out)[orow] = floats_to_chunk<BF16>(av);
-  } else {
-    float *p = c.partials + ((unit * sh.part_total + task.w) * 2) * D + ch * EPC;
+    K_out[(long long)mine.x * LPR + ch] = floats_to_chunk<BF16>(ak);
+    V_out[(long long)mine.x * LPR + ch] = floats_to_chunk<BF16>(av);
+    return;
+  }
+
+  // ---- a larger task: all row groups of the wave stream its rows
+  {
+    const int4 task = seq_tasks[wl];  // (slot, first member, count, partial index or -1)
+    const int *members = seq_members + task.y;
+    float ak[EPC], av[EPC];
 #pragma unroll
-    for (int e = 0; e < EPC; e += 4) {
-      *reinterpret_cast<float4 *>(p + e) = make_float4(ak[e], ak[e + 1], ak[e + 2], ak[e + 3]);
-      *reinterpret_cast<float4 *>(p + D + e) = make_float4(av[e], av[e + 1], av[e + 2], av[e + 3]);
+    for (int e = 0; e < EPC; ++e) ak[e] = av[e] = 0.f;
+    const bool single = task.w < 0;
+    const int pivot_tok = kept[task.x];
+    float wsum = 0.f;        // weighted merge: weights this row group has added
+    float pk[EPC], pss = 0.f;  // weighted merge: this lane's chunk of the pivot's key, its squared norm
+    if constexpr (WEIGHTED) {
+      chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], pk);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) pss = fmaf(pk[e], pk[e], pss);
+#pragma unroll
+      for (int o = LPR / 2; o >= 1; o >>= 1) pss += __shfl_xor(pss, o, 64);
     }
-    if (WEIGHTED && ch == 0) c.partial_w[unit * sh.part_total + task.w] = wsum;
+    if (single && rg == 0) {
+      if constexpr (WEIGHTED) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) ak[e] = pk[e];
+        wsum = 1.f;
+      } else {
+        chunk_to_floats<BF16>(K[(long long)pivot_tok * sh.ks_tok + ch], ak);
+      }
+      chunk_to_floats<BF16>(V[(long long)pivot_tok * sh.ks_tok + ch], av);
+    }
+    for (int j0 = rg; j0 < task.z; j0 += RPL * U) {
+      int tokv[U];
+      uint4 kc[U], vc[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = j0 + u * RPL;
+        tokv[u] = j < task.z ? members[j] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (tokv[u] >= 0) {
+          kc[u] = K[(long long)tokv[u] * sh.ks_tok + ch];
+          vc[u] = V[(long long)tokv[u] * sh.ks_tok + ch];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        // every lane takes part in the exchanges below, so rows past the end count as zero rows
+        float fk[EPC], fv[EPC];
+        const bool real = tokv[u] >= 0;
+        if (real) {
+          chunk_to_floats<BF16>(kc[u], fk);
+          chunk_to_floats<BF16>(vc[u], fv);
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) fk[e] = fv[e] = 0.f;
+        }
+        if constexpr (WEIGHTED) {
+          float dot = 0.f, ss = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { dot = fmaf(fk[e], pk[e], dot); ss = fmaf(fk[e], fk[e], ss); }
+#pragma unroll
+          for (int o = LPR / 2; o >= 1; o >>= 1) { dot += __shfl_xor(dot, o, 64); ss += __shfl_xor(ss, o, 64); }
+          const float w = ss > 0.f && pss > 0.f ? fmaxf(dot / (sqrtf(ss) * sqrtf(pss)), 0.f) : 0.f;
+          wsum += w;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { ak[e] = fmaf(w, fk[e], ak[e]); av[e] = fmaf(w, fv[e], av[e]); }
+        } else if (real) {
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) { ak[e] += fk[e]; av[e] += fv[e]; }
+        }
+      }
+    }
+    // fold the row groups (fixed tree)
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        ak[e] += __shfl_xor(ak[e], o, 64);
+        av[e] += __shfl_xor(av[e], o, 64);
+      }
+      if constexpr (WEIGHTED) wsum += __shfl_xor(wsum, o, 64);
+    }
+    if (rg != 0) return;
+    if (single) {
+      const float den = WEIGHTED ? wsum : (float)(1 + task.z);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) { ak[e] = ak[e] / den; av[e] = av[e] / den; }
+      K_out[(long long)task.x * LPR + ch] = floats_to_chunk<BF16>(ak);
+      V_out[(long long)task.x * LPR + ch] = floats_to_chunk<BF16>(av);
+    } else {
+      float *p = c.partials + ((unit * sh.part_total + task.w) * 2) * D + ch * EPC;
+#pragma unroll
+      for (int e = 0; e < EPC; e += 4) {
+        *reinterpret_cast<float4 *>(p + e) = make_float4(ak[e], ak[e + 1], ak[e + 2], ak[e + 3]);
+        *reinterpret_cast<float4 *>(p + D + e) = make_float4(av[e], av[e + 1], av[e + 2], av[e + 3]);
+      }
+      if (WEIGHTED && ch == 0) c.partial_w[unit * sh.part_total + task.w] = wsum;
+    }
   }
 }
 
