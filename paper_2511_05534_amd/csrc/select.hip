@@ -14,6 +14,8 @@
 // One workgroup per (sequence, kv head, layer).  The B-th largest importance is found by a
 // 4-pass radix select on the float bit patterns (importances are non-negative, so the bits
 // order like the values); a block-wide ordered scan then compacts the pivots.
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 #include "profile.h"
@@ -29,6 +31,7 @@ template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   __shared__ SelectScratch<kThreads> scratch;
+  __shared__ SmallSelectScratch<kThreads> scratch_regs;
   __shared__ float lds_head[kThreads];
   __shared__ float sh_rho;
   const Shape &sh = c.sh;
@@ -72,7 +75,20 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
   const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
-  select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
+  // Up to 16 keys per thread stay in registers for the four radix passes and the compaction (one
+  // trip to memory instead of five); longer sequences read their keys again in every pass.
+  auto from_registers = [&](auto kpt_tag) {
+    constexpr int KPT = decltype(kpt_tag)::value;
+    unsigned keys[KPT];
+    const int i0 = threadIdx.x * KPT;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) keys[j] = i0 + j < s.L ? imp[i0 + j] : 0u;
+    select_top_b_regs<kThreads, KPT>(keys, s.L, sh.W, s.B, kept, assign, scratch_regs);
+  };
+  if (s.L <= 4 * kThreads) from_registers(std::integral_constant<int, 4>{});
+  else if (s.L <= 8 * kThreads) from_registers(std::integral_constant<int, 8>{});
+  else if (s.L <= 16 * kThreads) from_registers(std::integral_constant<int, 16>{});
+  else select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
   __syncthreads();  // kept[] is read back below; sh_rho is set
   const bool cross = (sh_rho > sh.theta) != (sh.invert_flow != 0);
 

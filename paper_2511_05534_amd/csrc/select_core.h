@@ -199,17 +199,19 @@ struct SmallSelectScratch {
   int wave_sums[THREADS / 64 + 1];
 };
 
-// Top-B split for L <= 4 * THREADS with few barriers: every thread keeps its four consecutive
+// Top-B split for L <= KPT * THREADS with few barriers: every thread keeps its KPT consecutive
 // keys in registers, each radix pass costs one barrier (the 256-bin scan is repeated by every
 // wave on its own instead of being shared), and the compaction is one block scan.
-// keys4: the thread's keys 4t..4t+3 (anything where 4t+j >= L).  Same results as select_top_b.
-template <int THREADS>
-__device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], int L, int W, int B, int *kept,
-                                                   int *assign, SmallSelectScratch<THREADS> &sc) {
+// keys: the thread's keys KPT t .. KPT t + KPT - 1 (anything where the index is >= L).  kept and
+// assign may be LDS or global.  Same results as select_top_b.
+template <int THREADS, int KPT>
+__device__ __forceinline__ void select_top_b_regs(const unsigned (&keys)[KPT], int L, int W, int B, int *kept,
+                                                  int *assign, SmallSelectScratch<THREADS> &sc) {
+  static_assert(KPT * THREADS <= 65535, "the packed scan keeps two 16-bit counts");
   const int lane = threadIdx.x & 63;
   const int nbody = L - W;
   const int need = B - W;
-  const int i0 = threadIdx.x * 4;
+  const int i0 = threadIdx.x * KPT;
   unsigned thr = 0xffffffffu;
   int need_eq = 0;
   for (int i = threadIdx.x; i < 4 * 256; i += THREADS) (&sc.hist[0][0])[i] = 0;
@@ -222,9 +224,9 @@ __device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], i
       const int shift = 24 - 8 * pass;
       int *hist = sc.hist[pass];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const bool act = i0 + j < nbody && (keys4[j] & mask) == prefix;
-        const int dg = (keys4[j] >> shift) & 255;
+      for (int j = 0; j < KPT; ++j) {
+        const bool act = i0 + j < nbody && (keys[j] & mask) == prefix;
+        const int dg = (keys[j] >> shift) & 255;
         const unsigned long long am = __ballot(act);
         if (am) {  // a whole wave on one digit is the common case for the exponent byte
           const int first = __ffsll((long long)am) - 1;
@@ -262,20 +264,22 @@ __device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], i
     thr = prefix;
     need_eq = remaining;
   }
-  // ordered compaction: one block scan over (above, equal) counts of the threads' four keys
-  int gt4 = 0, eq4 = 0;
-  bool gtj[4], eqj[4];
+  // ordered compaction: one block scan over (above, equal) counts of the threads' keys
+  int gtn = 0, eqn = 0;
+  unsigned gtm = 0, eqm = 0;  // bit j: key j is above / equal to the threshold
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < KPT; ++j) {
     const int i = i0 + j;
-    gtj[j] = i < L && (i >= nbody || keys4[j] > thr);
-    eqj[j] = i < nbody && keys4[j] == thr;
-    gt4 += gtj[j];
-    eq4 += eqj[j];
+    const bool gt = i < L && (i >= nbody || keys[j] > thr);
+    const bool eq = i < nbody && keys[j] == thr;
+    gtm |= (unsigned)gt << j;
+    eqm |= (unsigned)eq << j;
+    gtn += gt;
+    eqn += eq;
   }
   // block-wide exclusive scan of the packed counts: a wave scan on the DPP path, then the totals of
   // the earlier waves (one barrier)
-  const int packed = gt4 | (eq4 << 16);
+  const int packed = gtn | (eqn << 16);
   const int inc = wave_inclusive_scan(packed);
   if (lane == 63) sc.wave_sums[threadIdx.x >> 6] = inc;
   __syncthreads();
@@ -283,17 +287,24 @@ __device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], i
   for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += sc.wave_sums[w];
   int gt_before = before & 0xffff, eq_before = before >> 16;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < KPT; ++j) {
     const int i = i0 + j;
+    const bool gt = (gtm >> j) & 1u, eq = (eqm >> j) & 1u;
     if (i < L) {
-      const bool is_kept = gtj[j] || (eqj[j] && eq_before < need_eq);
+      const bool is_kept = gt || (eq && eq_before < need_eq);
       const int slot = gt_before + min(eq_before, need_eq);
       if (is_kept) kept[slot] = i;
       assign[i] = is_kept ? slot : -2;
     }
-    gt_before += gtj[j];
-    eq_before += eqj[j];
+    gt_before += gt;
+    eq_before += eq;
   }
+}
+
+template <int THREADS>
+__device__ __forceinline__ void select_top_b_small(const unsigned (&keys4)[4], int L, int W, int B, int *kept,
+                                                   int *assign, SmallSelectScratch<THREADS> &sc) {
+  select_top_b_regs<THREADS, 4>(keys4, L, W, B, kept, assign, sc);
 }
 
 // The need-th largest of keys[0..nbody) (nbody <= 1024), found by ONE wave that holds 16 keys
