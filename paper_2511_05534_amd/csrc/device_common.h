@@ -111,6 +111,12 @@ __device__ __forceinline__ int wave_sum_int(int v) {
   return v;
 }
 
+// For grids whose x extent counts sequences (or a fixed number of workgroups per sequence) and whose
+// y, z are kv head and layer: workgroups go to the eight XCDs in turn by their linear index, so a
+// batch of eight would pin each sequence, long ones included, to one XCD.  Rotating x by the other
+// two coordinates spreads every sequence over all XCDs; for fixed (y, z) it is still a bijection.
+__device__ __forceinline__ int rotated_block_x() { return (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x; }
+
 // sequence that owns flat index x given an increasing cumulative table cu[0..batch]
 __device__ __forceinline__ int find_seq(const int *__restrict__ cu, int batch, int x) {
   int lo = 0, hi = batch;  // invariant: cu[lo] <= x < cu[hi]

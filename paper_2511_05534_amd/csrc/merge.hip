@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
   __shared__ unsigned long long lds_wave[kCsrWaves + 1];
   const Shape &sh = c.sh;
   const int *meta = c.meta;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const int b = rotated_block_x(), gkv = blockIdx.y, l = blockIdx.z;
   const SeqInfo s = load_seq(meta, b);
   const long long unit = (long long)l * sh.Hkv + gkv;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -391,12 +391,13 @@ __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
   const Shape &sh = c.sh;
   const int *meta = c.meta;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int b = blockIdx.x / kFoldGroups;
+  const int bx = rotated_block_x();
+  const int b = bx / kFoldGroups;
   const int gkv = blockIdx.y, l = blockIdx.z;
   const long long unit = (long long)l * sh.Hkv + gkv;
   const int n_multi = c.n_multi[unit * sh.batch + b];
   const int q0 = (meta + meta[MW_OFF_CU_MULTI])[b];
-  for (int qm = (blockIdx.x % kFoldGroups) * 4 + wave; qm < n_multi; qm += kFoldGroups * 4) {
+  for (int qm = (bx % kFoldGroups) * 4 + wave; qm < n_multi; qm += kFoldGroups * 4) {
     const int q = q0 + qm;
     const SeqInfo s = load_seq(meta, b);
     const int4 e4 = c.multi[unit * sh.multi_total + q];  // (slot, first partial, partials, members)

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
 // ---- pass 2: fold the tiles of a sequence ----------------------------------------------
 __global__ __launch_bounds__(256) void score_combine_kernel(Ctx c) {
   const Shape &sh = c.sh;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const int b = rotated_block_x(), gkv = blockIdx.y, l = blockIdx.z;
   const int *cu = c.meta + c.meta[MW_OFF_CU_SCORE];
   const int x0 = cu[b], x1 = cu[b + 1];
   const float2 *in = c.part_stats + (long long)(l * sh.Hkv + gkv) * sh.tiles_score * sh.R_pad;

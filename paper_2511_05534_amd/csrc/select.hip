@@ -20,6 +20,7 @@
 #include "kernels.h"
 #include "profile.h"
 #include "select_core.h"
+#include "trace.h"
 
 namespace flowmm {
 
@@ -28,7 +29,8 @@ namespace {
 constexpr int kThreads = 1024;
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
+// eight waves per SIMD (at most 64 vector and 96 scalar registers): two workgroups share a compute unit
+__global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   __shared__ SelectScratch<kThreads> scratch;
   __shared__ SmallSelectScratch<kThreads> scratch_regs;
@@ -36,9 +38,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
   __shared__ float sh_rho;
   const Shape &sh = c.sh;
   const int *meta = c.meta;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z;
+  const int b = rotated_block_x(), gkv = blockIdx.y, l = blockIdx.z;
   const SeqInfo s = load_seq(meta, b);
   const long long unit = (long long)l * sh.Hkv + gkv;
+  TRACE(0);
 
   // ---- flow: every workgroup of the layer folds the same numbers in the same order -------------
   {
@@ -71,12 +74,14 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
     }
   }
 
+  TRACE(1);
   // ---- top-B split -----------------------------------------------------------------------------
   const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
-  // Up to 16 keys per thread stay in registers for the four radix passes and the compaction (one
-  // trip to memory instead of five); longer sequences read their keys again in every pass.
+  // Up to 8 keys per thread stay in registers for the four radix passes and the compaction (one
+  // trip to memory instead of five); longer sequences read their keys again in every pass (with 16
+  // keys per thread the passes got longer than the reads they save).
   auto from_registers = [&](auto kpt_tag) {
     constexpr int KPT = decltype(kpt_tag)::value;
     unsigned keys[KPT];
@@ -87,9 +92,9 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
   };
   if (s.L <= 4 * kThreads) from_registers(std::integral_constant<int, 4>{});
   else if (s.L <= 8 * kThreads) from_registers(std::integral_constant<int, 8>{});
-  else if (s.L <= 16 * kThreads) from_registers(std::integral_constant<int, 16>{});
   else select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
   __syncthreads();  // kept[] is read back below; sh_rho is set
+  TRACE(2);
   const bool cross = (sh_rho > sh.theta) != (sh.invert_flow != 0);
 
   // ---- lists of eligible pivots per token class --------------------------------------------------
@@ -125,6 +130,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
     n[1] += tot >> 16;
   }
   __syncthreads();
+  TRACE(3);
   const int np[2] = {(n[0] + 31) & ~31, (n[1] + 31) & ~31};
 #pragma unroll
   for (int cls = 0; cls < 2; ++cls)
@@ -134,6 +140,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
     }
   if (threadIdx.x < 2) c.pl_n[(unit * sh.batch + b) * 2 + threadIdx.x] = np[threadIdx.x];
   __syncthreads();
+  TRACE(4);
   // rows and inverse norms: NCH lanes per row
   constexpr int RPP = kThreads / NCH;  // rows per pass; a multiple of 32, so a pass ends inside a padded list
   const int rl = threadIdx.x / NCH, ch = threadIdx.x % NCH;
@@ -165,9 +172,18 @@ __global__ __launch_bounds__(kThreads) void select_kernel(Ctx c) {
       }
     }
   }
+  TRACE(5);
 }
 
 }  // namespace
+
+#ifdef FLOWMM_TRACE
+}  // namespace flowmm
+extern "C" __attribute__((visibility("default"))) int flowmm_trace_set_select(void *p) {
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(flowmm::g_trace), &p, sizeof(p));
+}
+namespace flowmm {
+#endif
 
 hipError_t launch_select(const Ctx &c) {
   ProfScope ps(c.stream, KID_SELECT);

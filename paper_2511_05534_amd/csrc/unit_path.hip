@@ -81,7 +81,7 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
   __shared__ int sh_dropped;
 
   const Shape &sh = c.sh;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z + c.layer0;
+  const int b = rotated_block_x(), gkv = blockIdx.y, l = blockIdx.z + c.layer0;
   const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
@@ -548,7 +548,7 @@ __device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, ch
 template <int D>
 __global__ __launch_bounds__(kF2Threads) void unit_match_kernel(Ctx c, int b_pad) {
   extern __shared__ __align__(16) char lds_dyn[];
-  unit_flow_match_body<D>(c, b_pad, lds_dyn, blockIdx.x, blockIdx.y, blockIdx.z + c.layer0);
+  unit_flow_match_body<D>(c, b_pad, lds_dyn, rotated_block_x(), blockIdx.y, blockIdx.z + c.layer0);
 }
 
 // ============================ merge =========================================================
@@ -561,7 +561,7 @@ __global__ __launch_bounds__(kF3Threads) void unit_merge_kernel(Ctx c, int maxB,
   __shared__ long long lds_wave[kF3Waves + 1];
   __shared__ int sh_next;
   const Shape &sh = c.sh;
-  const int b = blockIdx.x, gkv = blockIdx.y, l = blockIdx.z + c.layer0;
+  const int b = rotated_block_x(), gkv = blockIdx.y, l = blockIdx.z + c.layer0;
   if constexpr (FLOW) {
     static_assert(kF2Threads == kF3Threads, "one workgroup runs both bodies");
     unit_flow_match_body<D>(c, b_pad, reinterpret_cast<char *>(lds_i), b, gkv, l);
