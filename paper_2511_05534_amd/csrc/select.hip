@@ -27,6 +27,7 @@ namespace flowmm {
 namespace {
 
 constexpr int kThreads = 1024;
+constexpr int kSelectRegisterKeys = 16 * kThreads;  // longest sequence whose keys stay in registers
 
 template <bool BF16, int D>
 // eight waves per SIMD (at most 64 vector and 96 scalar registers): two workgroups share a compute unit
@@ -34,6 +35,7 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   __shared__ SelectScratch<kThreads> scratch;
   __shared__ SmallSelectScratch<kThreads> scratch_regs;
+  extern __shared__ unsigned lds_keys[];  // [min(maxL, kSelectRegisterKeys)] keys, then assignments
   __shared__ float lds_head[kThreads];
   __shared__ float sh_rho;
   const Shape &sh = c.sh;
@@ -79,19 +81,29 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   int *assign = c.assign + unit * sh.T + s.tok_off;
-  // Up to 8 keys per thread stay in registers for the four radix passes and the compaction (one
-  // trip to memory instead of five); longer sequences read their keys again in every pass (with 16
-  // keys per thread the passes got longer than the reads they save).
+  // Up to 16 keys per thread stay in registers for the four radix passes and the compaction (one
+  // trip to memory instead of five); longer sequences read their keys again in every pass.  A
+  // thread owns consecutive keys (the compaction is then one block scan), which is no shape to talk
+  // to memory in: keys come in and assignments go out through LDS, in coalesced rows.
   auto from_registers = [&](auto kpt_tag) {
     constexpr int KPT = decltype(kpt_tag)::value;
+    for (int i = threadIdx.x; i < s.L; i += kThreads) lds_keys[i] = imp[i];
+    __syncthreads();
     unsigned keys[KPT];
     const int i0 = threadIdx.x * KPT;
 #pragma unroll
-    for (int j = 0; j < KPT; ++j) keys[j] = i0 + j < s.L ? imp[i0 + j] : 0u;
-    select_top_b_regs<kThreads, KPT>(keys, s.L, sh.W, s.B, kept, assign, scratch_regs);
+    for (int j = 0; j < KPT; ++j) keys[j] = i0 + j < s.L ? lds_keys[i0 + j] : 0u;
+    // the same LDS words take the assignments (the call starts with a barrier of its own)
+    int *lds_assign = reinterpret_cast<int *>(lds_keys);
+    select_top_b_regs<kThreads, KPT>(keys, s.L, sh.W, s.B, kept, lds_assign, scratch_regs);
+    __syncthreads();
+    for (int i = threadIdx.x; i < s.L; i += kThreads) assign[i] = lds_assign[i];
   };
-  if (s.L <= 4 * kThreads) from_registers(std::integral_constant<int, 4>{});
-  else if (s.L <= 8 * kThreads) from_registers(std::integral_constant<int, 8>{});
+  // the launch reserves LDS for the longest sequence, or none when that one is too long
+  const bool staged = sh.maxL <= kSelectRegisterKeys;
+  if (staged && s.L <= 4 * kThreads) from_registers(std::integral_constant<int, 4>{});
+  else if (staged && s.L <= 8 * kThreads) from_registers(std::integral_constant<int, 8>{});
+  else if (staged) from_registers(std::integral_constant<int, 16>{});
   else select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
   __syncthreads();  // kept[] is read back below; sh_rho is set
   TRACE(2);
@@ -185,17 +197,24 @@ extern "C" __attribute__((visibility("default"))) int flowmm_trace_set_select(vo
 namespace flowmm {
 #endif
 
-hipError_t launch_select(const Ctx &c) {
+namespace {
+
+template <bool BF16, int D>
+hipError_t launch_select_t(const Ctx &c) {
+  const size_t lds = c.sh.maxL <= kSelectRegisterKeys ? (size_t)c.sh.maxL * 4 : 0;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel<BF16, D>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_SELECT);
-  const dim3 grid(c.sh.batch, c.sh.Hkv, c.sh.n_layers);
-  if (c.sh.bf16) {
-    if (c.sh.d == 128) select_kernel<true, 128><<<grid, kThreads, 0, c.stream>>>(c);
-    else select_kernel<true, 64><<<grid, kThreads, 0, c.stream>>>(c);
-  } else {
-    if (c.sh.d == 128) select_kernel<false, 128><<<grid, kThreads, 0, c.stream>>>(c);
-    else select_kernel<false, 64><<<grid, kThreads, 0, c.stream>>>(c);
-  }
+  select_kernel<BF16, D><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kThreads, lds, c.stream>>>(c);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_select(const Ctx &c) {
+  if (c.sh.bf16) return c.sh.d == 128 ? launch_select_t<true, 128>(c) : launch_select_t<true, 64>(c);
+  return c.sh.d == 128 ? launch_select_t<false, 128>(c) : launch_select_t<false, 64>(c);
 }
 
 }  // namespace flowmm

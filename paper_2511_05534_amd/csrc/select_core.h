@@ -225,10 +225,25 @@ __device__ __forceinline__ void select_top_b_regs(const unsigned (&keys)[KPT], i
       int *hist = sc.hist[pass];
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
-        const bool act = i0 + j < nbody && (keys[j] & mask) == prefix;
+        bool act = i0 + j < nbody && (keys[j] & mask) == prefix;
         const int dg = (keys[j] >> shift) & 255;
-        const unsigned long long am = __ballot(act);
-        if (am) {  // a whole wave on one digit is the common case for the exponent byte
+        unsigned long long am = __ballot(act);
+        if (KPT > 4 && pass == 0) {
+          // The exponent byte: a few digits per wave, and all waves add to the same few bins, where
+          // additions take their turns.  Lanes with the same digit add once, through their first lane;
+          // after four distinct digits the lanes that are left add by themselves.
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (!am) break;
+            const int first = __ffsll((long long)am) - 1;
+            const int d0 = __builtin_amdgcn_readlane(dg, first);
+            const unsigned long long same = __ballot(act && dg == d0);
+            if (lane == first) atomicAdd(&hist[d0], __popcll(same));
+            act = act && dg != d0;
+            am &= ~same;
+          }
+          if (act) atomicAdd(&hist[dg], 1);
+        } else if (am) {  // a whole wave on one digit is the common case for the exponent byte
           const int first = __ffsll((long long)am) - 1;
           const int d0 = __builtin_amdgcn_readlane(dg, first);
           if (__ballot(act && dg == d0) == am) {
