@@ -50,6 +50,13 @@ SMALL_CASES = {
     "unit_32_spans": dict(Hq=2, Hkv=1, W=16, n_layers=1, pct=(12,), spans=(tuple([20, 10] * 15 + [25, 17]),)),
     "more_spans_than_the_unit_path_takes": dict(Hq=2, Hkv=1, W=16, n_layers=1, pct=(12,),
                                                 spans=(tuple([20, 10] * 16 + [25, 17]),)),
+    # the top-B split keeps 4, 8 or 16 keys per thread in registers, or none beyond 16384 tokens (then for
+    # every sequence of the batch)
+    "select_8_keys_per_thread": dict(Hq=2, Hkv=1, d=64, W=16, n_layers=1, pct=(6,), spans=((300, 5000, 700),)),
+    "select_16_keys_per_thread": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, pct=(4,), spans=((400, 9000, 1100),)),
+    "select_keys_from_memory": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, pct=(3,), spans=((500, 15000, 1000),)),
+    "select_long_and_short_in_a_batch": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, pct=(3, 10),
+                                             spans=((500, 15000, 1000), (40, 300, 60))),
 }
 
 
