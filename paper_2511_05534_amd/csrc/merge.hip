@@ -23,6 +23,7 @@ namespace flowmm {
 namespace {
 
 constexpr int kCsrThreads = kCsrWaves * 64;
+constexpr int kCsrAhead = 4;   // rounds of 64 tokens a walking wave loads ahead
 constexpr int kSmallTask = 4;  // a slot with fewer members is merged by one row group (pivot + members = loads in flight)
 
 // Exclusive scan over the workgroup of a 64-bit value that packs several small counters (their
@@ -96,14 +97,26 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
   for (int i = threadIdx.x; i < s.B * NW; i += kCsrThreads) lds_tbl[i] = 0;
   __syncthreads();
 
-  // pass 1: members of each slot inside each wave's token range
+  // pass 1: members of each slot inside each wave's token range (kCsrAhead rounds of 64 tokens have
+  // their two dependent loads in flight together)
   if (wave < NW) {
-    for (int i0 = r0; i0 < r1; i0 += 64) {
-      const int i = i0 + lane;
-      const int slot = i < r1 ? assign[i] : -1;
-      const bool member = slot >= 0 && kept[slot] != i;
-      const unsigned long long m = same_slot_mask(member, slot, nbits);
-      if (member && (m & ((1ull << lane) - 1)) == 0) lds_tbl[slot * NW + wave] += __popcll(m);
+    for (int i0 = r0; i0 < r1; i0 += 64 * kCsrAhead) {
+      int slotv[kCsrAhead], keptv[kCsrAhead];
+#pragma unroll
+      for (int u = 0; u < kCsrAhead; ++u) {
+        const int i = i0 + 64 * u + lane;
+        slotv[u] = i < r1 ? assign[i] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < kCsrAhead; ++u) keptv[u] = slotv[u] >= 0 ? kept[slotv[u]] : -1;
+#pragma unroll
+      for (int u = 0; u < kCsrAhead; ++u) {
+        if (i0 + 64 * u >= r1) break;
+        const int i = i0 + 64 * u + lane, slot = slotv[u];
+        const bool member = slot >= 0 && keptv[u] != i;
+        const unsigned long long m = same_slot_mask(member, slot, nbits);
+        if (member && (m & ((1ull << lane) - 1)) == 0) lds_tbl[slot * NW + wave] += __popcll(m);
+      }
     }
   }
   __syncthreads();
@@ -162,16 +175,27 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
 
   // pass 2: write the members, ascending inside every slot
   if (wave < NW) {
-    for (int i0 = r0; i0 < r1; i0 += 64) {
-      const int i = i0 + lane;
-      const int slot = i < r1 ? assign[i] : -1;
-      const bool member = slot >= 0 && kept[slot] != i;
-      const unsigned long long m = same_slot_mask(member, slot, nbits);
-      const unsigned long long below = m & ((1ull << lane) - 1);
-      if (member) {
-        const int cur = lds_tbl[slot * NW + wave];
-        members[cur + __popcll(below)] = i;
-        if (below == 0) lds_tbl[slot * NW + wave] = cur + __popcll(m);
+    for (int i0 = r0; i0 < r1; i0 += 64 * kCsrAhead) {
+      int slotv[kCsrAhead], keptv[kCsrAhead];
+#pragma unroll
+      for (int u = 0; u < kCsrAhead; ++u) {
+        const int i = i0 + 64 * u + lane;
+        slotv[u] = i < r1 ? assign[i] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < kCsrAhead; ++u) keptv[u] = slotv[u] >= 0 ? kept[slotv[u]] : -1;
+#pragma unroll
+      for (int u = 0; u < kCsrAhead; ++u) {
+        if (i0 + 64 * u >= r1) break;
+        const int i = i0 + 64 * u + lane, slot = slotv[u];
+        const bool member = slot >= 0 && keptv[u] != i;
+        const unsigned long long m = same_slot_mask(member, slot, nbits);
+        const unsigned long long below = m & ((1ull << lane) - 1);
+        if (member) {
+          const int cur = lds_tbl[slot * NW + wave];
+          members[cur + __popcll(below)] = i;
+          if (below == 0) lds_tbl[slot * NW + wave] = cur + __popcll(m);
+        }
       }
     }
   }
