@@ -69,7 +69,9 @@ __device__ __forceinline__ unsigned long long same_slot_mask(bool member, int sl
 
 // at most 64 registers: two workgroups of 16 waves then share a compute unit
 __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw_shift) {
-  extern __shared__ int lds_tbl[];  // [B][NW] per-wave counts, later write cursors
+  // [NW][B] per-wave counts, later write cursors; the slot runs fastest, so that the slots of a wave's 64
+  // tokens and the 1024 slots of a scan step fall on different banks
+  extern __shared__ int lds_tbl[];
   __shared__ unsigned long long lds_wave[kCsrWaves + 1];
   const Shape &sh = c.sh;
   const int *meta = c.meta;
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
         const int i = i0 + 64 * u + lane, slot = slotv[u];
         const bool member = slot >= 0 && keptv[u] != i;
         const unsigned long long m = same_slot_mask(member, slot, nbits);
-        if (member && (m & ((1ull << lane) - 1)) == 0) lds_tbl[slot * NW + wave] += __popcll(m);
+        if (member && (m & ((1ull << lane) - 1)) == 0) lds_tbl[wave * s.B + slot] += __popcll(m);
       }
     }
   }
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
     const int slot = s0 + threadIdx.x;
     int n = 0;
     if (slot < s.B)
-      for (int w = 0; w < NW; ++w) n += lds_tbl[slot * NW + w];
+      for (int w = 0; w < NW; ++w) n += lds_tbl[w * s.B + slot];
     const int nt = slot < s.B ? max(1, (n + kTaskChunk - 1) / kTaskChunk) : 0;
     const int is_multi = nt > 1;
     const int is_small = slot < s.B && n < kSmallTask;
@@ -148,8 +150,8 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
       seg_off[slot] = seg;
       int base = seg;
       for (int w = 0; w < NW; ++w) {
-        const int t = lds_tbl[slot * NW + w];
-        lds_tbl[slot * NW + w] = base;
+        const int t = lds_tbl[w * s.B + slot];
+        lds_tbl[w * s.B + slot] = base;
         base += t;
       }
       if (is_small) tasks[sb] = make_int4(slot, seg, n, -1);
@@ -192,9 +194,9 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
         const unsigned long long m = same_slot_mask(member, slot, nbits);
         const unsigned long long below = m & ((1ull << lane) - 1);
         if (member) {
-          const int cur = lds_tbl[slot * NW + wave];
+          const int cur = lds_tbl[wave * s.B + slot];
           members[cur + __popcll(below)] = i;
-          if (below == 0) lds_tbl[slot * NW + wave] = cur + __popcll(m);
+          if (below == 0) lds_tbl[wave * s.B + slot] = cur + __popcll(m);
         }
       }
     }
