@@ -26,18 +26,20 @@ namespace {
 
 constexpr int kThreads = kMatchWaves * 64;
 
-// Direct global -> LDS load: lane i of the wave fetches BYTES bytes from its own global address and
-// they land at lds_base + i * BYTES (lds_base wave-uniform).  Issued as inline assembly so that the
-// compiler does not wait for it before unrelated LDS reads (it cannot tell the two LDS buffers
-// apart; nothing else in these kernels uses M0); the caller waits with s_waitcnt vmcnt(0) and a barrier before reading the data.
+// Direct global -> LDS load: lane i of the wave fetches BYTES bytes from base + byte_off (base
+// wave-uniform, in scalar registers; the lane's part is a 32-bit offset, so no lane keeps a 64-bit
+// address) and they land at lds_base + i * BYTES (lds_base wave-uniform).  Issued as inline assembly so
+// that the compiler does not wait for it before unrelated LDS reads (it cannot tell the two LDS
+// buffers apart; nothing else in these kernels uses M0); the caller waits with s_waitcnt vmcnt(0) and
+// a barrier before reading the data.
 typedef __attribute__((address_space(3))) void lds_void;
 template <int BYTES>
-__device__ __forceinline__ void load_to_lds(const void *gptr, void *lds_base) {
+__device__ __forceinline__ void load_to_lds(const void *base, unsigned byte_off, void *lds_base) {
   const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
   if constexpr (BYTES == 16)
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
   else
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
 }
 
 // sum of squares of a chunk added to s; bf16 pairs go through the two-element dot product instruction
@@ -120,9 +122,9 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
     uint4 *dst = lds_rows + buf * ROWS * RS;
     const int nchunks = rows * RS;  // the tile is a plain copy of that part of the pack
     for (int q0 = wave * 64; q0 < nchunks; q0 += kThreads)
-      if (q0 + lane < nchunks) load_to_lds<16>(src + q0 + lane, dst + q0);
+      if (q0 + lane < nchunks) load_to_lds<16>(src, (unsigned)(q0 + lane) * 16u, dst + q0);
     if (wave * 64 + lane < rows)
-      load_to_lds<4>(pl_w + r0 + wave * 64 + lane, lds_w + buf * ROWS + wave * 64);
+      load_to_lds<4>(pl_w + r0, (unsigned)(wave * 64 + lane) * 4u, lds_w + buf * ROWS + wave * 64);
   };
   if (ntiles > 0) stage(0, 0);
 
