@@ -57,14 +57,13 @@ __global__ __launch_bounds__(kFThreads, 2) void flow_exact_kernel(Ctx c, FlowExa
   {
     const uint4 *Q = reinterpret_cast<const uint4 *>(a.Q) + (long long)l * a.qs_layer + (long long)h * a.qs_head +
                      (long long)(s.tok_off + q0) * a.qs_tok;
-    const uint4 *zero = reinterpret_cast<const uint4 *>(meta + MW_ZERO16);
     const int total = kQT * RS;
     for (int qi0 = wave * 64; qi0 < total; qi0 += kFThreads) {
       const int qi = qi0 + lane;
       if (qi < total) {
         const int row = qi / RS, ch = qi - row * RS;
-        const uint4 *src = (q0 + row < L && ch < NCH) ? Q + (long long)row * a.qs_tok + ch : zero;
-        load16_to_lds(src, ldsq + qi0);
+        if (q0 + row < L && ch < NCH) load16_to_lds(Q, (unsigned)(row * a.qs_tok + ch) * 16u, ldsq + qi0);
+        else ldsq[qi] = make_uint4(0, 0, 0, 0);  // rows past the end, the padding chunk of every row
       }
     }
   }

@@ -68,6 +68,10 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
       return fail(FLOWMM_EINVAL, "strides must be non-negative multiples of 16 bytes (%d elements)", epc);
   if (p->k_stride_token < p->head_dim || p->q_stride_token < p->head_dim)
     return fail(FLOWMM_EINVAL, "token strides must be at least head_dim");
+  // the kernels address the window queries of one (layer, kv head, sequence) with 32-bit byte offsets
+  if (((int64_t)(p->n_q_heads / p->n_kv_heads - 1) * p->q_stride_head + (int64_t)(p->window - 1) * p->q_stride_token +
+       p->head_dim) * es >= (int64_t)1 << 32)
+    return fail(FLOWMM_EUNSUPPORTED, "the window queries of one kv head span 4 GiB or more");
 
   Shape &sh = lo.sh;
   sh.n_layers = p->n_layers; sh.Hq = p->n_q_heads; sh.Hkv = p->n_kv_heads; sh.G = sh.Hq / sh.Hkv;
@@ -422,6 +426,9 @@ FLOWMM_API flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K
     if (strides[i] < 0 || strides[i] % epc != 0)
       return fail(FLOWMM_EINVAL, "strides must be non-negative multiples of 16 bytes (%d elements)", epc);
   if (qf_stride_token < lo.sh.d) return fail(FLOWMM_EINVAL, "token strides must be at least head_dim");
+  // a tile of kFlowQueryTile query rows is addressed with 32-bit byte offsets
+  if (((int64_t)(kFlowQueryTile - 1) * qf_stride_token + lo.sh.d) * (lo.sh.bf16 ? 2 : 4) >= (int64_t)1 << 32)
+    return fail(FLOWMM_EUNSUPPORTED, "256 query rows span 4 GiB or more");
   if (workspace_bytes < lo.workspace_bytes)
     return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
   flowmm_plan_buffers none;

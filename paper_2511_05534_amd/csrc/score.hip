@@ -66,7 +66,6 @@ __device__ __forceinline__ void stage_queries(const Ctx &c, const TileCtx &t, ui
   const Shape &sh = c.sh;
   const uint4 *Q = reinterpret_cast<const uint4 *>(c.Q) + (long long)t.l * sh.qs_layer +
                    (long long)(t.gkv * sh.G) * sh.qs_head + (long long)(t.b * sh.W) * sh.qs_tok;
-  const uint4 *zero = reinterpret_cast<const uint4 *>(c.meta + MW_ZERO16);
   const int total = sh.R_pad * RS;
   // chunk q of the LDS image is chunk ch of row r of head g; q advances by the workgroup size per
   // trip, so (g, r, ch) are carried along instead of being divided out again
@@ -76,9 +75,10 @@ __device__ __forceinline__ void stage_queries(const Ctx &c, const TileCtx &t, ui
   int g = row / sh.W_pad, r = row - g * sh.W_pad;
   for (int q0 = t.wave * 64; q0 < total; q0 += kThreads) {
     if (q0 + t.lane < total) {
-      const uint4 *src = zero;
-      if (r < sh.W && ch < NCH) src = Q + (long long)g * sh.qs_head + (long long)r * sh.qs_tok + ch;
-      load16_to_lds(src, ldsq + q0);
+      if (r < sh.W && ch < NCH)
+        load16_to_lds(Q, (unsigned)(g * sh.qs_head + r * sh.qs_tok + ch) * 16u, ldsq + q0);
+      else
+        ldsq[q0 + t.lane] = make_uint4(0, 0, 0, 0);  // padding rows and the padding chunk of every row
     }
     ch += kChStep;
     r += kRowStep;

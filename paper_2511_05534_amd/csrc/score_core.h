@@ -5,13 +5,15 @@
 
 namespace flowmm {
 
-// lane i of the wave fetches 16 bytes from its own global address; they land at lds_base + 16 i
-// (lds_base wave-uniform).  Inline assembly, so the compiler does not wait for it before unrelated
-// LDS traffic (nothing else here uses M0); the caller waits with s_waitcnt vmcnt(0) and a barrier.
+// lane i of the wave fetches 16 bytes from base + byte_off (base wave-uniform, in scalar registers;
+// the lane's part is a 32-bit offset, so no lane keeps a 64-bit address); they land at
+// lds_base + 16 i (lds_base wave-uniform).  Lanes that are switched off leave their 16 bytes alone.
+// Inline assembly, so the compiler does not wait for it before unrelated LDS traffic (nothing else
+// here uses M0); the caller waits with s_waitcnt vmcnt(0) and a barrier.
 typedef __attribute__((address_space(3))) void lds_void;
-__device__ __forceinline__ void load16_to_lds(const void *gptr, void *lds_base) {
+__device__ __forceinline__ void load16_to_lds(const void *base, unsigned byte_off, void *lds_base) {
   const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
 }
 
 // The products of one block of 32 query rows with this wave's keys.  KEYS_AS_ROWS: accumulator
