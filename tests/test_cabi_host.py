@@ -68,6 +68,8 @@ BAD = [
     (dict(n_q_heads=64, n_kv_heads=1, window=128, budgets=[130, 140]), fb.FLOWMM_EUNSUPPORTED, "LDS"),
     (dict(seqlens=[300, 0], budgets=[30, 0]), fb.FLOWMM_EINVAL, "increasing"),
     (dict(flags=8), fb.FLOWMM_EINVAL, "flags"),
+    # the two query heads of a kv head 5 GiB apart: beyond the kernels' 32-bit offsets
+    (dict(q_strides=(1 << 34, 5 << 29, 128)), fb.FLOWMM_EUNSUPPORTED, "4 GiB"),
 ]
 
 
