@@ -23,7 +23,9 @@
  *     base + l*stride_layer + g*stride_head + t*stride_token + c   (elements, c contiguous).
  *     Q holds only the window rows: token index b*W + r is row r (prompt position L_b-W+r) of
  *     sequence b; heads are query heads; query head h reads KV head h / (Hq/Hkv).
- *   - Device pointers must be 16-byte aligned, strides multiples of 16 bytes.
+ *   - Device pointers must be 16-byte aligned, strides multiples of 16 bytes.  The window queries
+ *     of one (layer, kv head, sequence) must lie within 4 GiB of each other (FLOWMM_EUNSUPPORTED
+ *     otherwise): (Hq/Hkv - 1)*q_stride_head + (W - 1)*q_stride_token + head_dim elements.
  *   - Errors in the arguments are found on the host before anything is launched; the call
  *     then returns a code and flowmm_last_error() describes it.  Nothing was enqueued.
  */
@@ -139,7 +141,8 @@ flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K, const voi
  *                                           / (total mass of query r),
  *   mode[l][b] = FLOWMM_MODE_CROSS iff rho > theta (inverted under FLOWMM_FLAG_INVERT_FLOW).
  * Q_full [Lyr][Hq][T][d]: the query of every packed token, dtype of K, read through the three
- * strides given here (elements; head_dim contiguous).  K, p, workspace (size from
+ * strides given here (elements; head_dim contiguous; 256 consecutive tokens of a head must lie
+ * within 4 GiB, FLOWMM_EUNSUPPORTED otherwise).  K, p, workspace (size from
  * flowmm_plan_sizes), stream and the rules for errors as in flowmm_plan; window, budgets and tau
  * are validated but not used.  rho, mode: device, [Lyr][batch].  Cost grows with L^2: this is a
  * measurement, and a way to supply the strategy when the prefill can provide all queries. */
