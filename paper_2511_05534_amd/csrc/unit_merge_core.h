@@ -14,6 +14,14 @@
 
 namespace flowmm {
 
+// 16-byte chunk number `chunk` behind a wave-uniform base: the lane's part of the address is a 32-bit
+// byte offset (the unit-resident path is only taken when a sequence's rows lie within 4 GiB), which
+// spares the 64-bit multiply-add per row that a pointer per lane costs.
+template <typename T>
+__device__ __forceinline__ T chunk_at(const void *base, unsigned chunk) {
+  return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + (size_t)(chunk * 16u));
+}
+
 constexpr int kF3Threads = 256;
 constexpr int kF3Waves = kF3Threads / 64;
 constexpr int kF3Chunks = 4;   // 64-token chunks a wave walks: ceil(1024 / 4 waves / 64)
@@ -165,6 +173,7 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   const long long head_off = (long long)l * sh.ks_layer + (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + head_off;
   const uint4 *V = reinterpret_cast<const uint4 *>(c.V) + head_off;
+  const unsigned kst = (unsigned)sh.ks_tok;
   uint4 *Ko = reinterpret_cast<uint4 *>(c.K_out) + (unit * sh.SB + s.kept_off) * LPR;
   uint4 *Vo = reinterpret_cast<uint4 *>(c.V_out) + (unit * sh.SB + s.kept_off) * LPR;
   constexpr int kGroups = kF3Waves * RPL;
@@ -176,7 +185,6 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   // through a native vector type: arrays of the uint4 class would be kept in scratch memory.)
   {
     typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-    const u32x4_t *Kc = reinterpret_cast<const u32x4_t *>(K), *Vc = reinterpret_cast<const u32x4_t *>(V);
     u32x4_t *Koc = reinterpret_cast<u32x4_t *>(Ko), *Voc = reinterpret_cast<u32x4_t *>(Vo);
     int idx = gid;
     for (; idx + (U - 1) * kGroups < n_copy; idx += U * kGroups) {
@@ -187,8 +195,8 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int tok = lds_kept[slotv[u]];
-        kc[u] = Kc[(long long)tok * sh.ks_tok + ch];
-        vc[u] = Vc[(long long)tok * sh.ks_tok + ch];
+        kc[u] = chunk_at<u32x4_t>(K, (unsigned)tok * kst + ch);
+        vc[u] = chunk_at<u32x4_t>(V, (unsigned)tok * kst + ch);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -199,8 +207,8 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
     for (; idx < n_copy; idx += kGroups) {
       const int slot = copies[idx];
       const int tok = lds_kept[slot];
-      const u32x4_t kc = Kc[(long long)tok * sh.ks_tok + ch];
-      const u32x4_t vc = Vc[(long long)tok * sh.ks_tok + ch];
+      const u32x4_t kc = chunk_at<u32x4_t>(K, (unsigned)tok * kst + ch);
+      const u32x4_t vc = chunk_at<u32x4_t>(V, (unsigned)tok * kst + ch);
       Koc[(long long)slot * LPR + ch] = kc;
       Voc[(long long)slot * LPR + ch] = vc;
     }
@@ -241,8 +249,8 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
       if constexpr (WEIGHTED) pkc = K[(long long)pivot_tok * sh.ks_tok + ch];  // the cosines need the pivot's key
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        kc[u] = K[(long long)tokv[u] * sh.ks_tok + ch];
-        vc[u] = V[(long long)tokv[u] * sh.ks_tok + ch];
+        kc[u] = chunk_at<uint4>(K, (unsigned)tokv[u] * kst + ch);
+        vc[u] = chunk_at<uint4>(V, (unsigned)tokv[u] * kst + ch);
       }
       if constexpr (WEIGHTED) {
         float pk[EPC], fk[U][EPC], dot[U], ss[U];

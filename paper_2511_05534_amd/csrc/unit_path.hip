@@ -652,6 +652,7 @@ namespace flowmm {
 bool unit_path_fits(const Shape &sh) {
   if (!sh.bf16 || sh.maxL > 1024 || sh.R_pad > 64 || sh.maxB > 256 || sh.Hq > 4096) return false;
   if (sh.batch > kInlineSeqs || sh.n_spans > kInlineSpans) return false;  // metadata must fit the kernel arguments
+  if (sh.ks_tok * 16 * 1024 >= (1ll << 32)) return false;  // the merge addresses a sequence's rows with 32-bit offsets
   const int b_pad = (sh.maxB + 31) / 32 * 32;
   if (match_lds_bytes(sh, b_pad) > 150 * 1024 || plan_lds_bytes(sh, b_pad) > 150 * 1024) return false;
   if ((size_t)merge_lds_layout(sh.maxB, sh.maxE, sh.d).total_bytes > 150 * 1024) return false;
