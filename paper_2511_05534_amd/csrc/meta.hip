@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void meta_upload_kernel(MetaChunk chunk, int *
 
 // one workgroup per span: the modality byte of its tokens, and their places in the sequence's
 // class order (all text positions ascending, then all image positions ascending)
-__global__ __launch_bounds__(256) void expand_modality_kernel(const int *meta, uint8_t *mod, int *cls_order) {
+__device__ __forceinline__ void expand_span(const int *meta, uint8_t *mod, int *cls_order) {
   const int batch = meta[MW_BATCH];
   const int *spans = meta + meta[MW_OFF_SPANS] + 3 * blockIdx.x;
   // owner sequence: the one whose span range contains this span
@@ -38,9 +38,29 @@ __global__ __launch_bounds__(256) void expand_modality_kernel(const int *meta, u
   }
 }
 
+__global__ __launch_bounds__(256) void expand_modality_kernel(const int *meta, uint8_t *mod, int *cls_order) {
+  expand_span(meta, mod, cls_order);
+}
+
+// Both in one launch when the metadata fits one kernel-argument block: every workgroup reads the
+// words from its arguments (nothing waits for the copy in the workspace), workgroup 0 also writes them.
+__global__ __launch_bounds__(256) void meta_upload_expand_kernel(MetaChunk chunk, int *dst, int n, uint8_t *mod,
+                                                                 int *cls_order) {
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i < n; i += 256) dst[i] = chunk.w[i];
+  expand_span(chunk.w, mod, cls_order);
+}
+
 }  // namespace
 
 hipError_t launch_meta_upload(const Ctx &c, const int *words, int n_words, bool expand_modality) {
+  if (expand_modality && n_words <= kMetaChunkWords && words[MW_N_SPANS] > 0) {
+    MetaChunk chunk;
+    for (int i = 0; i < n_words; ++i) chunk.w[i] = words[i];
+    ProfScope ps(c.stream, KID_META_UPLOAD);
+    meta_upload_expand_kernel<<<words[MW_N_SPANS], 256, 0, c.stream>>>(chunk, c.meta, n_words, c.mod, c.cls_order);
+    return hipGetLastError();
+  }
   for (int off = 0; off < n_words; off += kMetaChunkWords) {
     MetaChunk chunk;
     const int n = n_words - off < kMetaChunkWords ? n_words - off : kMetaChunkWords;
