@@ -169,12 +169,14 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
   for (int sub = 0; sub < KS; ++sub) { best[sub] = 0u; bblk[sub] = 0; }
 
   // A block is 32 list rows against this wave's tokens: every fragment read from LDS feeds KS matrix
-  // instructions (one per token group), fragments are requested kAhead steps before they are used,
+  // instructions (one per token group), the next fragment is requested before the current one is used,
   // then the KS x 16 dot products of each lane are folded into the running maxima.  The two waves
   // that share a SIMD overlap one's matrix phase with the other's folding.
   constexpr int NBLK = ROWS / 32;   // blocks per LDS tile
   constexpr int kBlockBytes = 32 * RS * 16;
-  constexpr int kAhead = NF < 3 ? NF : 3;
+  // one fragment ahead: with four waves per SIMD the others cover the LDS latency, and the registers
+  // a deeper queue takes had to be found in scratch memory
+  constexpr int kAhead = 1;
   const int fa = (n * RS + half) * 16;  // byte offset of this lane's first fragment inside a block
   const char *lds_bytes = reinterpret_cast<const char *>(lds);
   for (int t = 0; t < ntiles; ++t) {
