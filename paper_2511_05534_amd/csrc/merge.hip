@@ -435,18 +435,29 @@ __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
       den = 1.f;  // the pivot's own weight, then the partial sums in task order
       for (int pi = 0; pi < e4.z; ++pi) den += c.partial_w[unit * sh.part_total + e4.y + pi];
     }
-    // lanes [0, NCH) fold K chunks, lanes [NCH, 2 NCH) fold V chunks
-    for (int idx = lane; idx < 2 * NCH; idx += 64) {
+    // 2 NCH lanes cover the K and V chunks of the row; the wave's kParts such lane groups share the
+    // slot's partials (consecutive ranges, in task order inside each; group 0 starts from the pivot's
+    // row) and their sums are added in a fixed tree: the longest chain is 1/kParts of the slot's
+    constexpr int kParts = 64 / (2 * NCH);
+    {
+      const int part_id = lane / (2 * NCH), idx = lane % (2 * NCH);
       const int tensor = idx / NCH, ch = idx % NCH;
       const uint4 *src = reinterpret_cast<const uint4 *>(tensor ? c.V : c.K) + head_off;
       float acc[EPC];
-      chunk_to_floats<BF16>(src[ch], acc);
+      if (part_id == 0) {
+        chunk_to_floats<BF16>(src[ch], acc);
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
+      }
+      const int per = (e4.z + kParts - 1) / kParts;
+      const int pbeg = part_id * per, pend = min(e4.z, pbeg + per);
       constexpr int U = 8;  // partials in flight; they are added in task order all the same
-      for (int p0 = 0; p0 < e4.z; p0 += U) {
+      for (int p0 = pbeg; p0 < pend; p0 += U) {
         float part[U][EPC];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          if (p0 + u < e4.z) {
+          if (p0 + u < pend) {
             const float *pp = c.partials + ((unit * sh.part_total + e4.y + p0 + u) * 2 + tensor) * D + ch * EPC;
 #pragma unroll
             for (int e = 0; e < EPC; e += 4) {
@@ -457,16 +468,22 @@ __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          if (p0 + u < e4.z) {
+          if (p0 + u < pend) {
 #pragma unroll
             for (int e = 0; e < EPC; ++e) acc[e] += part[u][e];
           }
         }
       }
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) acc[e] = acc[e] / den;
-      const long long orow = (unit * sh.SB + s.kept_off + e4.x) * NCH + ch;
-      reinterpret_cast<uint4 *>(tensor ? c.V_out : c.K_out)[orow] = floats_to_chunk<BF16>(acc);
+      for (int o = 2 * NCH; o < 64; o <<= 1)
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+      if (part_id == 0) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] = acc[e] / den;
+        const long long orow = (unit * sh.SB + s.kept_off + e4.x) * NCH + ch;
+        reinterpret_cast<uint4 *>(tensor ? c.V_out : c.K_out)[orow] = floats_to_chunk<BF16>(acc);
+      }
     }
   }
 }
