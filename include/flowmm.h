@@ -119,8 +119,10 @@ flowmm_status flowmm_plan(const flowmm_params *p, const void *K, const void *Q_w
 
 /* K_out, V_out [Lyr][Hkv][SB][d] contiguous, dtype of the inputs:
  *   out[slot] = (row[kept_idx[slot]] + sum of rows assigned to slot) / (1 + their number),
- * accumulated in fp32 in ascending token order and rounded to nearest-even; a pivot nobody
- * merges into is copied bit for bit.  Outputs must not overlap K or V. */
+ * accumulated in fp32 in an order that depends only on the shapes and the plan (so a call is
+ * reproducible; short prompts add in ascending token order, long ones by groups of rows and a fixed
+ * tree, and the two can differ in the last bit of a result) and rounded to nearest-even; a pivot
+ * nobody merges into is copied bit for bit.  Outputs must not overlap K or V. */
 flowmm_status flowmm_merge(const flowmm_params *p, const flowmm_plan_buffers *plan, const void *K,
                            const void *V, void *K_out, void *V_out, void *workspace,
                            size_t workspace_bytes, void *stream);
