@@ -260,12 +260,13 @@ __device__ __forceinline__ void select_top_b_regs(const unsigned (&keys)[KPT], i
       for (int j = 0; j < 4; ++j) c4[j] = hist[255 - 4 * lane - j];
       const int mine = c4[0] + c4[1] + c4[2] + c4[3];
       int before = wave_inclusive_scan(mine) - mine;  // keys in higher bins
-      int digit = -1, rem_new = 0;
+      int digit = -1, rem_new = 0, in_bin = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (digit < 0 && before < remaining && remaining <= before + c4[j]) {
           digit = 255 - 4 * lane - j;
           rem_new = remaining - before;
+          in_bin = c4[j];
         }
         before += c4[j];
       }
@@ -273,8 +274,14 @@ __device__ __forceinline__ void select_top_b_regs(const unsigned (&keys)[KPT], i
       const int src = __ffsll((long long)found) - 1;
       digit = __builtin_amdgcn_readlane(digit, src);
       remaining = __builtin_amdgcn_readlane(rem_new, src);
+      in_bin = __builtin_amdgcn_readlane(in_bin, src);
       prefix |= (unsigned)digit << shift;
       mask |= 255u << shift;
+      // Every key of the bin is wanted: the digits below need not be looked at.  The prefix with zeros
+      // under it then serves as the threshold (the keys of the bin are above it or equal to it, and as
+      // many equal ones are wanted as the bin holds).  With float keys this ends most searches after
+      // the second or third pass: the bin of the B-th largest key rarely holds another key by then.
+      if (in_bin == remaining) break;
     }
     thr = prefix;
     need_eq = remaining;
