@@ -36,6 +36,11 @@ typedef __attribute__((address_space(3))) void lds_void;
 template <int BYTES>
 __device__ __forceinline__ void load_to_lds(const void *base, unsigned byte_off, void *lds_base) {
   const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
+  // the base goes through the first lane's copy of it: free when it already sits in scalar registers,
+  // and it keeps the operand a scalar pair when the compiler has lost track of its uniformity
+  const unsigned long long bits = (unsigned long long)(uintptr_t)base;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)bits), hi = __builtin_amdgcn_readfirstlane((unsigned)(bits >> 32));
+  base = reinterpret_cast<const void *>((uintptr_t)(((unsigned long long)hi << 32) | lo));
   if constexpr (BYTES == 16)
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
   else
