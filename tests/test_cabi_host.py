@@ -126,3 +126,17 @@ def test_pointer_checks_happen_before_any_launch():
 
 def test_last_error_is_never_null():
     assert isinstance(fb.load().flowmm_last_error(), bytes)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more ends with a message and a non-zero status
+    before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
