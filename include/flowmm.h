@@ -28,6 +28,11 @@
  *     otherwise): (Hq/Hkv - 1)*q_stride_head + (W - 1)*q_stride_token + head_dim elements.
  *   - Errors in the arguments are found on the host before anything is launched; the call
  *     then returns a code and flowmm_last_error() describes it.  Nothing was enqueued.
+ *   - Threads: every call is self-contained (no state is kept between calls beyond flags that say
+ *     which kernels had their LDS limit raised on which device, set once and never changed), so
+ *     host threads may call concurrently, each with its own stream, plan buffers, outputs and
+ *     workspace.  Two calls that share a workspace or an output must be ordered by the caller
+ *     (same stream, or events).  flowmm_last_error() is per thread.
  */
 #ifndef FLOWMM_H
 #define FLOWMM_H
@@ -166,18 +171,6 @@ flowmm_status flowmm_decode_attention(const flowmm_params *p, const void *q, con
 
 /* Message of the last failing call on this thread (static storage, never NULL). */
 const char *flowmm_last_error(void);
-
-/* ---- measurement support (no part of the method; used by the benchmark) --------------------
- * The library can bracket chosen kernels with HIP events on the launch stream.
- * flowmm_profile_select: names = "all", "" / NULL (off, the default) or a comma-separated list
- *   of kernel names as returned by flowmm_profile_kernel_name(0 .. count-1).
- * flowmm_profile_collect: waits for the recorded events (host-side wait on those events only),
- *   adds up milliseconds and launch counts per kernel id into the two host arrays (each
- *   flowmm_profile_kernel_count() long, either may be NULL) and forgets the records. */
-int flowmm_profile_kernel_count(void);
-const char *flowmm_profile_kernel_name(int id);
-void flowmm_profile_select(const char *names);
-flowmm_status flowmm_profile_collect(double *total_ms, long long *launches);
 
 #ifdef __cplusplus
 }

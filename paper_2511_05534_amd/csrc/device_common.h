@@ -111,6 +111,33 @@ __device__ __forceinline__ int wave_sum_int(int v) {
   return v;
 }
 
+// Direct global -> LDS load: lane i of the wave fetches BYTES (4 or 16) bytes from base + byte_off
+// (base wave-uniform, in scalar registers; the lane's part is a 32-bit offset, so no lane keeps a
+// 64-bit address) and they land at lds_base + i * BYTES (lds_base wave-uniform).  Lanes that are
+// switched off leave their bytes alone.  Issued as inline assembly so that the compiler does not
+// wait for it before unrelated LDS reads (it cannot tell two LDS buffers apart); the statement
+// sets M0 and says so in its clobber list (the compiler keeps M0 out of register allocation and
+// warns about any such entry; the entry is still what orders its own M0 writes around this one).
+// The caller waits with s_waitcnt vmcnt(0) and a barrier before reading the data.
+typedef __attribute__((address_space(3))) void lds_void;
+template <int BYTES>
+__device__ __forceinline__ void load_to_lds(const void *base, unsigned byte_off, void *lds_base) {
+  static_assert(BYTES == 4 || BYTES == 16, "one dword or four per lane");
+  const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
+  // the base goes through the first lane's copy of it: free when it already sits in scalar registers,
+  // and it keeps the operand a scalar pair when the compiler has lost track of its uniformity
+  const unsigned long long bits = (unsigned long long)(uintptr_t)base;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)bits), hi = __builtin_amdgcn_readfirstlane((unsigned)(bits >> 32));
+  base = reinterpret_cast<const void *>((uintptr_t)(((unsigned long long)hi << 32) | lo));
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+  if constexpr (BYTES == 16)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+#pragma clang diagnostic pop
+}
+
 // For grids whose x extent counts sequences (or a fixed number of workgroups per sequence) and whose
 // y, z are kv head and layer: workgroups go to the eight XCDs in turn by their linear index, so a
 // batch of eight would pin each sequence, long ones included, to one XCD.  Rotating x by the other

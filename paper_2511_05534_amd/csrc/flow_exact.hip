@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kFThreads, 2) void flow_exact_kernel(Ctx c, FlowExa
       const int qi = qi0 + lane;
       if (qi < total) {
         const int row = qi / RS, ch = qi - row * RS;
-        if (q0 + row < L && ch < NCH) load16_to_lds(Q, (unsigned)(row * a.qs_tok + ch) * 16u, ldsq + qi0);
+        if (q0 + row < L && ch < NCH) load_to_lds<16>(Q, (unsigned)(row * a.qs_tok + ch) * 16u, ldsq + qi0);
         else ldsq[qi] = make_uint4(0, 0, 0, 0);  // rows past the end, the padding chunk of every row
       }
     }
@@ -225,8 +225,7 @@ hipError_t launch_flow_exact_t(const Ctx &c, const FlowExactArgs &a) {
   size_t lds = (size_t)kQT * (NCH + 1) * 16;  // the query rows; later the statistics in the same space
   const size_t lds_stats = (size_t)kFWaves * kQT * sizeof(float4) + (size_t)kQT * 4;
   if (lds_stats > lds) lds = lds_stats;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(flow_exact_kernel<BF16, D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<flow_exact_kernel<BF16, D>>();
   if (e != hipSuccess) return e;
   {
     ProfScope ps(c.stream, KID_FLOW_EXACT);

@@ -37,7 +37,7 @@ struct Layout {
   size_t kv_extent_bytes, q_extent_bytes;
 };
 
-constexpr size_t kLdsLimit = 160 * 1024;
+constexpr size_t kLdsLimit = kLdsBytes;
 
 flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
   if (!p) return fail(FLOWMM_EINVAL, "params is NULL");

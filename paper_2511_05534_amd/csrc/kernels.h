@@ -4,9 +4,34 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "layout.h"
 
 namespace flowmm {
+
+// LDS of a compute unit, and the most one workgroup may ask for (static plus dynamic)
+constexpr size_t kLdsBytes = 160 * 1024;
+
+// A kernel that wants more than 64 KB of dynamic LDS needs its cap raised first.  The cap belongs
+// to the function (per device), not to a launch, so it is raised once per kernel and device to all the
+// LDS there is beside the kernel's static share: no later call changes it, whatever shapes other
+// host threads launch at the same time.
+template <auto Kernel>
+hipError_t allow_full_lds() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<bool> done[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < kMaxDevices && done[dev].load(std::memory_order_acquire)) return hipSuccess;
+  hipFuncAttributes at;
+  if ((e = hipFuncGetAttributes(&at, reinterpret_cast<const void *>(Kernel))) != hipSuccess) return e;
+  const size_t room = kLdsBytes > at.sharedSizeBytes ? kLdsBytes - at.sharedSizeBytes : 0;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)room);
+  if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[dev].store(true, std::memory_order_release);
+  return e;
+}
 
 struct Ctx {
   Shape sh;

@@ -26,27 +26,6 @@ namespace {
 
 constexpr int kThreads = kMatchWaves * 64;
 
-// Direct global -> LDS load: lane i of the wave fetches BYTES bytes from base + byte_off (base
-// wave-uniform, in scalar registers; the lane's part is a 32-bit offset, so no lane keeps a 64-bit
-// address) and they land at lds_base + i * BYTES (lds_base wave-uniform).  Issued as inline assembly so
-// that the compiler does not wait for it before unrelated LDS reads (it cannot tell the two LDS
-// buffers apart; nothing else in these kernels uses M0); the caller waits with s_waitcnt vmcnt(0) and
-// a barrier before reading the data.
-typedef __attribute__((address_space(3))) void lds_void;
-template <int BYTES>
-__device__ __forceinline__ void load_to_lds(const void *base, unsigned byte_off, void *lds_base) {
-  const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
-  // the base goes through the first lane's copy of it: free when it already sits in scalar registers,
-  // and it keeps the operand a scalar pair when the compiler has lost track of its uniformity
-  const unsigned long long bits = (unsigned long long)(uintptr_t)base;
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)bits), hi = __builtin_amdgcn_readfirstlane((unsigned)(bits >> 32));
-  base = reinterpret_cast<const void *>((uintptr_t)(((unsigned long long)hi << 32) | lo));
-  if constexpr (BYTES == 16)
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
-  else
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
-}
-
 // sum of squares of a chunk added to s; bf16 pairs go through the two-element dot product instruction
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 template <bool BF16>
@@ -274,8 +253,7 @@ hipError_t launch_match_t(const Ctx &c) {
   const Shape &sh = c.sh;
   const size_t lds = 2 * (size_t)ROWS * (NCH + 1) * 16 + 2 * ROWS * sizeof(float) +
                      (size_t)match_tile_tokens(BF16) * sizeof(int);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(match_kernel<BF16, D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<match_kernel<BF16, D>>();
   if (e != hipSuccess) return e;
   const int units = sh.n_layers * sh.Hkv;
   const long long grid = (long long)((units + 7) / 8) * 8 * sh.tiles_match;

@@ -491,8 +491,7 @@ __global__ __launch_bounds__(256) void merge_fold_kernel(Ctx c) {
 template <bool BF16, int D, bool WEIGHTED>
 hipError_t launch_merge_w(const Ctx &c, int nw_shift, size_t lds) {
   const Shape &sh = c.sh;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_csr_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<merge_csr_kernel>();
   if (e != hipSuccess) return e;
   {
     ProfScope ps(c.stream, KID_MERGE_CSR);

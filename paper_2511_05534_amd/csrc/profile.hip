@@ -5,7 +5,7 @@
 #include <mutex>
 #include <vector>
 
-#include "../../include/flowmm.h"
+#include "../../include/flowmm_profile.h"
 
 namespace flowmm {
 

@@ -16,7 +16,6 @@
 #include "kernels.h"
 #include "profile.h"
 #include "score_core.h"
-#include "trace.h"
 
 namespace flowmm {
 
@@ -76,7 +75,7 @@ __device__ __forceinline__ void stage_queries(const Ctx &c, const TileCtx &t, ui
   for (int q0 = t.wave * 64; q0 < total; q0 += kThreads) {
     if (q0 + t.lane < total) {
       if (r < sh.W && ch < NCH)
-        load16_to_lds(Q, (unsigned)(g * sh.qs_head + r * sh.qs_tok + ch) * 16u, ldsq + q0);
+        load_to_lds<16>(Q, (unsigned)(g * sh.qs_head + r * sh.qs_tok + ch) * 16u, ldsq + q0);
       else
         ldsq[q0 + t.lane] = make_uint4(0, 0, 0, 0);  // padding rows and the padding chunk of every row
     }
@@ -164,29 +163,21 @@ __global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
   extern __shared__ uint4 lds[];
   const Shape &sh = c.sh;
   TileCtx t;
-  TRACE(0);
   if (!tile_ctx<score_tile_keys(BF16)>(c, t)) return;
   uint4 *ldsq = lds;
   float *lds_stats = reinterpret_cast<float *>(lds + sh.R_pad * (NCH + 1));  // [waves][R_pad]
-  TRACE(1);
   uint4 kf[KS][NF];
   load_keys<BF16, D, KS>(c, t, kf);  // the long way first (HBM); the query rows come from L2
-  TRACE(2);
   stage_queries<BF16, D>(c, t, ldsq);
-  TRACE(3);
   __builtin_amdgcn_s_waitcnt(0);
-  TRACE(4);
   __syncthreads();
-  TRACE(5);
   if (t.key0 < t.s.L) {  // waves past the end of the sequence have nothing to add
     if (t.masked) stats_body<BF16, D, KS, true>(c, t, kf, ldsq, lds_stats);
     else stats_body<BF16, D, KS, false>(c, t, kf, ldsq, lds_stats);
   } else {
     for (int row = t.lane; row < sh.R_pad; row += 64) lds_stats[t.wave * sh.R_pad + row] = -INFINITY;
   }
-  TRACE(6);
   __syncthreads();
-  TRACE(7);
   float2 *out = c.part_stats + ((long long)(t.l * sh.Hkv + t.gkv) * sh.tiles_score + t.x) * sh.R_pad;
   for (int row = threadIdx.x; row < sh.R_pad; row += kThreads) {
     float2 a = make_float2(lds_stats[row], 1.f);
@@ -195,7 +186,6 @@ __global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
     for (int w = 1; w < kScoreWaves; ++w) stat_combine(a.x, a.y, lds_stats[w * sh.R_pad + row], 1.f);
     out[row] = a;
   }
-  TRACE(8);
 }
 
 // ---- pass 2: fold the tiles of a sequence ----------------------------------------------
@@ -353,11 +343,9 @@ hipError_t launch_score_t(const Ctx &c) {
   const size_t lds1 = q_bytes + (size_t)kScoreWaves * sh.R_pad * sizeof(float);
   const size_t lds3 = q_bytes + (size_t)sh.R_pad * 4 + (size_t)sh.W_pad * 4 + (size_t)kScoreWaves * sh.G * 4;
   hipError_t e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_stats_kernel<BF16, D>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+  e = allow_full_lds<score_stats_kernel<BF16, D>>();
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_colsum_kernel<BF16, D>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3);
+  e = allow_full_lds<score_colsum_kernel<BF16, D>>();
   if (e != hipSuccess) return e;
   const int units = sh.n_layers * sh.Hkv;
   const long long grid = (long long)((units + 7) / 8) * 8 * sh.tiles_score;
@@ -378,14 +366,6 @@ hipError_t launch_score_t(const Ctx &c) {
 }
 
 }  // namespace
-
-#ifdef FLOWMM_TRACE
-}  // namespace flowmm
-extern "C" __attribute__((visibility("default"))) int flowmm_trace_set_score(void *p) {
-  return (int)hipMemcpyToSymbol(HIP_SYMBOL(flowmm::g_trace), &p, sizeof(p));
-}
-namespace flowmm {
-#endif
 
 size_t score_lds_bytes(const Shape &sh) {
   const int nch = sh.d * (sh.bf16 ? 2 : 4) / 16;

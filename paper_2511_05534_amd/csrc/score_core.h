@@ -5,22 +5,6 @@
 
 namespace flowmm {
 
-// lane i of the wave fetches 16 bytes from base + byte_off (base wave-uniform, in scalar registers;
-// the lane's part is a 32-bit offset, so no lane keeps a 64-bit address); they land at
-// lds_base + 16 i (lds_base wave-uniform).  Lanes that are switched off leave their 16 bytes alone.
-// Inline assembly, so the compiler does not wait for it before unrelated LDS traffic (nothing else
-// here uses M0); the caller waits with s_waitcnt vmcnt(0) and a barrier.
-typedef __attribute__((address_space(3))) void lds_void;
-__device__ __forceinline__ void load16_to_lds(const void *base, unsigned byte_off, void *lds_base) {
-  const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)lds_base);
-  // the base goes through the first lane's copy of it: free when it already sits in scalar registers,
-  // and it keeps the operand a scalar pair when the compiler has lost track of its uniformity
-  const unsigned long long bits = (unsigned long long)(uintptr_t)base;
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)bits), hi = __builtin_amdgcn_readfirstlane((unsigned)(bits >> 32));
-  base = reinterpret_cast<const void *>((uintptr_t)(((unsigned long long)hi << 32) | lo));
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory");
-}
-
 // The products of one block of 32 query rows with this wave's keys.  KEYS_AS_ROWS: accumulator
 // rows are keys and lane n owns query row n (pass 1); otherwise rows are query rows and lane n owns
 // key n of every group (pass 3).  Fragments are requested kAhead steps ahead, also across blocks.

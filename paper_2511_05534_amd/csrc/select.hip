@@ -20,7 +20,6 @@
 #include "kernels.h"
 #include "profile.h"
 #include "select_core.h"
-#include "trace.h"
 
 namespace flowmm {
 
@@ -43,7 +42,6 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   const int b = rotated_block_x(), gkv = blockIdx.y, l = blockIdx.z;
   const SeqInfo s = load_seq(meta, b);
   const long long unit = (long long)l * sh.Hkv + gkv;
-  TRACE(0);
 
   // ---- flow: every workgroup of the layer folds the same numbers in the same order -------------
   {
@@ -75,8 +73,6 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
       c.n_dropped[unit * sh.batch + b] = 0;
     }
   }
-
-  TRACE(1);
   // ---- top-B split -----------------------------------------------------------------------------
   const unsigned *imp = reinterpret_cast<const unsigned *>(c.importance) + unit * sh.T + s.tok_off;
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
@@ -106,7 +102,6 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   else if (staged) from_registers(std::integral_constant<int, 16>{});
   else select_top_b<kThreads>(imp, s.L, sh.W, s.B, kept, assign, scratch);
   __syncthreads();  // kept[] is read back below; sh_rho is set
-  TRACE(2);
   const bool cross = (sh_rho > sh.theta) != (sh.invert_flow != 0);
 
   // ---- lists of eligible pivots per token class --------------------------------------------------
@@ -142,7 +137,6 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
     n[1] += tot >> 16;
   }
   __syncthreads();
-  TRACE(3);
   const int np[2] = {(n[0] + 31) & ~31, (n[1] + 31) & ~31};
 #pragma unroll
   for (int cls = 0; cls < 2; ++cls)
@@ -152,7 +146,6 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
     }
   if (threadIdx.x < 2) c.pl_n[(unit * sh.batch + b) * 2 + threadIdx.x] = np[threadIdx.x];
   __syncthreads();
-  TRACE(4);
   // rows and inverse norms: NCH lanes per row
   constexpr int RPP = kThreads / NCH;  // rows per pass; a multiple of 32, so a pass ends inside a padded list
   const int rl = threadIdx.x / NCH, ch = threadIdx.x % NCH;
@@ -184,26 +177,16 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
       }
     }
   }
-  TRACE(5);
 }
 
 }  // namespace
-
-#ifdef FLOWMM_TRACE
-}  // namespace flowmm
-extern "C" __attribute__((visibility("default"))) int flowmm_trace_set_select(void *p) {
-  return (int)hipMemcpyToSymbol(HIP_SYMBOL(flowmm::g_trace), &p, sizeof(p));
-}
-namespace flowmm {
-#endif
 
 namespace {
 
 template <bool BF16, int D>
 hipError_t launch_select_t(const Ctx &c) {
   const size_t lds = c.sh.maxL <= kSelectRegisterKeys ? (size_t)c.sh.maxL * 4 : 0;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel<BF16, D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<select_kernel<BF16, D>>();
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_SELECT);
   select_kernel<BF16, D><<<dim3(c.sh.batch, c.sh.Hkv, c.sh.n_layers), kThreads, lds, c.stream>>>(c);

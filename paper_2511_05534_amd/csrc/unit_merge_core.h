@@ -8,10 +8,6 @@
 #include "kernels.h"
 #include "select_core.h"
 
-#ifndef TRACE
-#define TRACE(k)
-#endif
-
 namespace flowmm {
 
 // 16-byte chunk number `chunk` behind a wave-uniform base: the lane's part of the address is a 32-bit
@@ -89,8 +85,6 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
   const Shape &sh = c.sh;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   constexpr int NW = kF3Waves;
-
-  TRACE(8 + 0);
   int nbits = 0;
   while ((1 << nbits) < s.B) ++nbits;
   const int range = ((s.L + NW - 1) / NW + 63) & ~63;  // <= 64 * kF3Chunks since L <= 1024
@@ -118,7 +112,6 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
     if (member[k] && (same[k] & ((1ull << lane) - 1)) == 0) tbl[slot_of[k] * NW + wave] += __popcll(same[k]);
   }
   __syncthreads();
-  TRACE(8 + 1);
   int n_tasks, n_multi, n_copy;
   {  // one packed scan over the slots (B <= 256 <= threads): member offsets, multi-task slots,
      // their chunks, single-task slots and copy-only slots
@@ -158,7 +151,6 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
     }
   }
   __syncthreads();
-  TRACE(8 + 2);
 #pragma unroll
   for (int k = 0; k < kF3Chunks; ++k) {
     const unsigned long long below = same[k] & ((1ull << lane) - 1);
@@ -214,7 +206,6 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
     }
   }
   __syncthreads();
-  TRACE(8 + 3);
 
   // Every group works on its own task, one batch of U rows per trip of the loop, and takes the
   // next free task when it is done (large chunks come first in the list), so neither a long
@@ -319,9 +310,7 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
       }
     }
   }
-  TRACE(8 + 4);
   __syncthreads();
-  TRACE(8 + 5);
   // slots cut into several tasks: pivot row plus the partials in task order
   for (int qm = wave; qm < n_multi; qm += kF3Waves) {
     const int4 e4 = multi[qm];
@@ -347,7 +336,6 @@ __device__ __forceinline__ void unit_merge_body(const Ctx &c, const SeqInfo &s, 
       (tensor ? Vo : Ko)[(long long)e4.x * LPR + cch] = floats_to_chunk<kBF16>(acc);
     }
   }
-  TRACE(8 + 6);
 }
 
 }  // namespace flowmm

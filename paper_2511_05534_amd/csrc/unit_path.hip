@@ -15,7 +15,6 @@
 #include "kernels.h"
 #include "profile.h"
 #include "select_core.h"
-#include "trace.h"
 #include "unit_merge_core.h"
 
 namespace flowmm {
@@ -86,7 +85,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const long long unit = (long long)l * sh.Hkv + gkv;
-  TRACE(0);
 
   // ---- every key of the unit into registers ----------------------------------------------------
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
@@ -121,7 +119,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
     if (threadIdx.x == 0) sh_dropped = 0;
   }
   __syncthreads();
-  TRACE(1);
 
   const float cl = sh.scale_log2e;
   const int wmask = sh.W_pad - 1;  // W_pad is 32 or 64 here
@@ -179,7 +176,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
       if (half == 0) lds_stat[wave * ROWS + rb * 32 + n] = make_float2(m[rb], z[rb]);
     }
   }
-  TRACE(2);
   __syncthreads();
   if (threadIdx.x < ROWS) {
     float2 a = lds_stat[threadIdx.x];
@@ -192,7 +188,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
     lds_c[threadIdx.x] = ((int)threadIdx.x & wmask) < sh.W && a.y > 0.f ? a.x + __builtin_amdgcn_logf(a.y) : INFINITY;
   }
   __syncthreads();
-  TRACE(3);
 
   // ---- pass 2: probabilities reduced over the query rows; rows are query rows, lane n owns key n --
   {
@@ -260,7 +255,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
       }
     }
   }
-  TRACE(4);
   __syncthreads();
   if (wave < sh.G) {
     // query head `wave` owns the row blocks [wave*W_pad/32, (wave+1)*W_pad/32); lane t adds tile t's
@@ -286,7 +280,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
       lds_piv[(idx / NCH) * RS + idx % NCH] = make_uint4(0, 0, 0, 0);
   }
   __syncthreads();
-  TRACE(5);
   int *kept = c.kept_idx + unit * sh.SB + s.kept_off;
   for (int i = threadIdx.x; i < s.B; i += kPThreads) kept[i] = lds_kept[i];
 
@@ -314,7 +307,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
     }
   }
   __syncthreads();
-  TRACE(6);
 
   // ---- match as a cross-modal layer does ---------------------------------------------------------------
   // Each candidate is cosine * |token| (+ bias); its low four mantissa bits are replaced by 15 - i,
@@ -378,7 +370,6 @@ __global__ __launch_bounds__(WAVES * 64) void unit_plan_kernel(Ctx c, int b_pad)
   if (lane == 0 && dropped) atomicAdd(&sh_dropped, dropped);
   __syncthreads();
   if (threadIdx.x == 0) c.n_dropped[unit * sh.batch + b] = sh_dropped;
-  TRACE(7);
 }
 
 // ============================ flow (+ select + match of intra-modal layers) ====================
@@ -421,7 +412,6 @@ __device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, ch
   __shared__ int sh_dropped;
 
   const Shape &sh = c.sh;
-  TRACE(8);
   const SeqInfo s = inline_seq(c.inl, b);
   const int L = s.L;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
@@ -467,12 +457,10 @@ __device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, ch
     keys4[j] = i < L ? imp[i] : 0u;
     if (i < L) lds_keys[i] = keys4[j];
   }
-  TRACE(9);
   // top-B split (pivot list and pivot/non-pivot marks stay in LDS; the plan gets its copy below)
   select_top_b_small<kF2Threads>(keys4, L, sh.W, s.B, lds_kept, lds_assign, scratch);
   __syncthreads();
   for (int i = threadIdx.x; i < s.B; i += kF2Threads) kept[i] = lds_kept[i];
-  TRACE(10);
 
   // stage all pivots once: rows, inverse norms, eligibility per token modality
   constexpr int kRowsPerPass = kF2Threads / NCH;
@@ -495,7 +483,6 @@ __device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, ch
     }
   }
   __syncthreads();
-  TRACE(11);
 
   const int nblk = b_pad >> 5;
   int dropped = 0;
@@ -538,7 +525,6 @@ __device__ __forceinline__ void unit_flow_match_body(const Ctx &c, int b_pad, ch
       for (int f = 0; f < NF; ++f) kf[f] = nxt[f];
     }
   }
-  TRACE(12);
   dropped = wave_sum_int(dropped);
   if (lane == 0 && dropped) atomicAdd(&sh_dropped, dropped);
   __syncthreads();
@@ -580,8 +566,7 @@ size_t plan_lds_bytes(const Shape &sh, int b_pad) {
 
 template <int D, int RB, int NT, int WAVES>
 hipError_t launch_plan_k(const Ctx &c, int b_pad, size_t lds) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_plan_kernel<D, RB, NT, WAVES>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<unit_plan_kernel<D, RB, NT, WAVES>>();
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_UNIT_PLAN);
   unit_plan_kernel<D, RB, NT, WAVES><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), WAVES * 64, lds, c.stream>>>(c, b_pad);
@@ -611,8 +596,7 @@ template <int D>
 hipError_t launch_f2(const Ctx &c) {
   const int b_pad = (c.sh.maxB + 31) / 32 * 32;
   const size_t lds = match_lds_bytes(c.sh, b_pad);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_match_kernel<D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<unit_match_kernel<D>>();
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, KID_UNIT_MATCH);
   unit_match_kernel<D><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kF2Threads, lds, c.stream>>>(c, b_pad);
@@ -624,8 +608,7 @@ hipError_t launch_f3w(const Ctx &c) {
   const int b_pad = (c.sh.maxB + 31) / 32 * 32;
   size_t lds = (size_t)merge_lds_layout(c.sh.maxB, c.sh.maxE, D).total_bytes;
   if (FLOW && match_lds_bytes(c.sh, b_pad) > lds) lds = match_lds_bytes(c.sh, b_pad);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(unit_merge_kernel<D, U, FLOW, WEIGHTED>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_full_lds<unit_merge_kernel<D, U, FLOW, WEIGHTED>>();
   if (e != hipSuccess) return e;
   ProfScope ps(c.stream, FLOW ? KID_UNIT_FLOW_MERGE : KID_UNIT_MERGE);
   unit_merge_kernel<D, U, FLOW, WEIGHTED><<<dim3(c.sh.batch, c.sh.Hkv, c.layers), kF3Threads, lds, c.stream>>>(
@@ -640,14 +623,6 @@ hipError_t launch_f3(const Ctx &c) {
 }
 
 }  // namespace
-
-#ifdef FLOWMM_TRACE
-}  // namespace flowmm
-extern "C" __attribute__((visibility("default"))) int flowmm_trace_set(void *p) {
-  return (int)hipMemcpyToSymbol(HIP_SYMBOL(flowmm::g_trace), &p, sizeof(p));
-}
-namespace flowmm {
-#endif
 
 bool unit_path_fits(const Shape &sh) {
   if (!sh.bf16 || sh.maxL > 1024 || sh.R_pad > 64 || sh.maxB > 256 || sh.Hq > 4096) return false;

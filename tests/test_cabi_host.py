@@ -14,8 +14,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "flowmm.h")).read()
-    declared = set(re.findall(r"\b(flowmm_[a-z_]+)\s*\(", header))
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
+    declared = set(re.findall(r"^[a-z_ ]*?\**\b(flowmm_[a-z_]+)\s*\(", header, flags=re.M))
     assert declared == set(fb.EXPORTS)
     lib = fb.load()
     for name in declared:

@@ -306,6 +306,92 @@ def test_match_zero_norm_rows(oracle):
     assert assign.tolist() == want.tolist()
 
 
+def np_match_top2(K, I, kept, mod, mode_cross, tau):
+    """Best and runner-up cosine of every token over its eligible pivots, from the dense masked matrix
+    (the cosine equation and the thresholded argmax of Sensitivity-Adaptive Token Matching): the two
+    largest entries of each row, counted with multiplicity; -inf where there is no such entry."""
+    K = K.astype(np.float64)
+    nrm = np.linalg.norm(K, axis=1)
+    Kn = np.divide(K, nrm[:, None], out=np.zeros_like(K), where=nrm[:, None] > 0)
+    U = Kn @ Kn[kept].T
+    elig = np.broadcast_to(I[kept][None, :] <= tau, U.shape).copy()
+    if not mode_cross:
+        elig &= mod[kept][None, :] == mod[:, None]
+    U = np.where(elig, U, -np.inf)
+    top = -np.sort(-U, axis=1)  # descending
+    second = top[:, 1] if U.shape[1] > 1 else np.full(len(U), -np.inf)
+    return top[:, 0], second
+
+
+@pytest.mark.parametrize("seed", range(3))
+@pytest.mark.parametrize("mode_cross", [0, 1])
+def test_match_margins_are_the_top_two_of_the_dense_cosine_matrix(oracle, seed, mode_cross):
+    """u_best / u_second decide which GPU mismatches the parity tests excuse: pin both to the dense
+    matrix, with a gate that removes some pivots and a modality restriction that removes others."""
+    K, V, Q, mod = rand_case(40 + seed, L=45, W=4)
+    I, _ = oracle.score(K, Q, mod)
+    for g in range(K.shape[0]):
+        kept = oracle.select(I[g], 4, 14)
+        tau = float(np.sort(I[g][kept])[-4])
+        _, _, ub, us = oracle.match(K[g], I[g], kept, mod, mode_cross, tau, with_margins=True)
+        wb, ws = np_match_top2(K[g], I[g], kept, mod, mode_cross, tau)
+        ev = np.setdiff1d(np.arange(45), kept)
+        assert np.allclose(ub[ev], wb[ev], rtol=0, atol=1e-12) and (np.isinf(ub[ev]) == np.isinf(wb[ev])).all()
+        assert np.allclose(us[ev], ws[ev], rtol=0, atol=1e-12) and (np.isinf(us[ev]) == np.isinf(ws[ev])).all()
+        assert (us[ev] <= ub[ev]).all()
+        # pivots are not matched: both margins are -inf for them
+        assert np.isneginf(ub[kept]).all() and np.isneginf(us[kept]).all()
+
+
+def test_match_margins_special_cases(oracle):
+    """Exact ties give margin 0 (the runner-up equals the best), a single eligible pivot has no
+    runner-up (-inf), no eligible pivot leaves both at -inf, and an earlier, larger candidate that is
+    later beaten becomes the runner-up (not the third best)."""
+    e = np.eye(4, dtype=np.float32)
+    K = np.zeros((9, 4), dtype=np.float32)
+    K[0] = e[0]                      # pivot slot 0
+    K[1] = 2.0 * e[0]                # pivot slot 1: same direction as slot 0 -> exact tie for every token
+    K[2] = e[1]                      # pivot slot 2
+    K[3] = e[2]                      # pivot slot 3 (made sensitive below)
+    K[4] = 3.0 * e[0]                # evicted: cosine 1 with slots 0 and 1 (tie), 0 with slot 2
+    K[5] = e[0] + e[1]               # evicted: cos 1/sqrt2 with slots 0, 1, 2 (three-way tie)
+    K[6] = e[1] + 0.5 * e[0]         # evicted: slot 2 best (2/sqrt5), slots 0/1 tie for second (1/sqrt5)
+    K[7] = e[2]                      # evicted: only the sensitive pivot points its way
+    K[8] = 0.0                       # evicted zero row: every cosine is 0
+    I = np.array([0.1, 0.1, 0.1, 0.9, 0, 0, 0, 0, 0], dtype=np.float64)
+    kept = np.array([0, 1, 2, 3], dtype=np.int32)
+    mod = np.array([0, 0, 1, 0, 0, 0, 1, 1, 0], dtype=np.int32)
+    a, nd, ub, us = oracle.match(K, I, kept, mod, 1, 0.5, with_margins=True)  # slot 3 is gated out
+    r5 = 1.0 / np.sqrt(5.0)
+    assert a[4] == 0 and ub[4] == 1.0 and us[4] == 1.0           # tie -> lower slot, margin 0
+    assert a[5] == 0 and abs(ub[5] - np.sqrt(0.5)) < 1e-15 and us[5] == ub[5]
+    assert a[6] == 2 and abs(ub[6] - 2 * r5) < 1e-15 and abs(us[6] - r5) < 1e-15
+    assert a[7] == 0 and ub[7] == 0.0 and us[7] == 0.0           # all remaining cosines are 0
+    assert a[8] == 0 and ub[8] == 0.0 and us[8] == 0.0
+    wb, ws = np_match_top2(K, I, kept, mod, 1, 0.5)
+    assert np.allclose(ub[4:], wb[4:], atol=1e-15) and np.allclose(us[4:], ws[4:], atol=1e-15)
+    # intra-modal: token 6 (image) sees only slot 2 -> no runner-up; token 7 (image) likewise;
+    # tokens 4, 5, 8 (text) see slots 0 and 1
+    a, nd, ub, us = oracle.match(K, I, kept, mod, 0, 0.5, with_margins=True)
+    assert a[6] == 2 and abs(ub[6] - 2 * r5) < 1e-15 and np.isneginf(us[6])
+    assert a[7] == 2 and ub[7] == 0.0 and np.isneginf(us[7])
+    assert a[4] == 0 and us[4] == 1.0
+    wb, ws = np_match_top2(K, I, kept, mod, 0, 0.5)
+    assert np.allclose(ub[4:], wb[4:], atol=1e-15)
+    assert (np.isneginf(us[4:]) == np.isneginf(ws[4:])).all()
+    # nothing eligible: both -inf and the token is dropped
+    a, nd, ub, us = oracle.match(K, I, kept, mod, 1, -1.0, with_margins=True)
+    assert (a[4:] == -1).all() and nd == 5 and np.isneginf(ub[4:]).all() and np.isneginf(us[4:]).all()
+    # descending candidates: the runner-up is the second one seen, not the last one beaten
+    K2 = np.zeros((4, 2), dtype=np.float32)
+    K2[0] = [1, 0]; K2[1] = [1, 1]; K2[2] = [0, 1]; K2[3] = [4, 1]
+    kept2 = np.array([0, 1, 2], dtype=np.int32)
+    I2 = np.zeros(4)
+    a, nd, ub, us = oracle.match(K2, I2, kept2, np.zeros(4, dtype=np.int32), 1, np.inf, with_margins=True)
+    n17 = np.sqrt(17.0)
+    assert a[3] == 0 and abs(ub[3] - 4 / n17) < 1e-15 and abs(us[3] - 5 / (n17 * np.sqrt(2.0))) < 1e-15
+
+
 # --------------------------------------------------------------------------------------
 # merge
 # --------------------------------------------------------------------------------------
