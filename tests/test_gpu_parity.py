@@ -75,12 +75,16 @@ def test_small_cases_match_oracle(oracle, name, path):
     print(rep, flush=True)
 
 
-def test_both_paths_agree_on_decisions():
+def test_both_paths_agree_on_decisions(oracle):
     """Same kept sets and assignments from the unit-resident and the generic kernels (decisions are
-    taken on fp32 numbers that may differ in the last bits, so compare where they are equal)."""
+    taken on fp32 numbers that may differ in the last bits, so compare where they are equal); where
+    they differ, each side's choice must lie inside the oracle's margin band (check_layer)."""
     w = small("paths", Hq=2, Hkv=2, spans=((35, 576, 64),), pct=(10,), n_layers=3)
     a = run_gpu(w, flags=0)
     b = run_gpu(w, flags=1)
+    for l in range(w.n_layers):
+        check_layer(oracle, w, a, l)
+        check_layer(oracle, w, b, l)
     same_I = (a["importance"] == b["importance"]).mean()
     print(f"identical importances: {same_I:.4f}", flush=True)
     assert np.allclose(a["importance"], b["importance"], rtol=1e-5, atol=0)
@@ -119,17 +123,21 @@ def test_ablation_variants_match_oracle(oracle, name, variant, path):
         print(rep, flush=True)
 
 
-def test_weighted_merge_of_identical_keys_is_the_uniform_mean():
-    """Every weight is 1 when all keys point the same way: both merge operators must agree."""
+def test_weighted_merge_of_identical_keys_is_the_uniform_mean(oracle):
+    """Every weight is 1 when all keys point the same way: both merge operators must agree with each
+    other and with the oracle (every cosine is 1: all assignments are exact ties, any eligible pivot is valid)."""
     import torch
     w = small("same_direction", Hq=2, Hkv=2, spans=((40, 300, 60),), n_layers=1)
     K, V, Q = upload(w)
     direction = torch.randn(w.head_dim, device=K.device).to(K.dtype)
     scale = (1 + torch.arange(K.shape[2], device=K.device) % 4).to(K.dtype)[None, None, :, None]  # exact multiples
     K = (direction[None, None, None, :] * scale).expand_as(K).contiguous()
+    host = (K[0].float().cpu().numpy(), V[0].float().cpu().numpy(), Q[0].float().cpu().numpy())
     for flags in (0, 1):
         a = run_gpu(w, tensors=(K, V, Q), flags=flags)
         b = run_gpu(w, tensors=(K, V, Q), flags=flags | 4)
+        check_layer(oracle, w, a, 0, tensors_np=host)
+        check_layer(oracle, w, b, 0, tensors_np=host, flags=4)
         assert (a["assign"] == b["assign"]).all()
         assert np.allclose(a["V_out"], b["V_out"], rtol=0, atol=2e-2)
         assert np.allclose(a["K_out"], b["K_out"], rtol=0, atol=2e-2 * 4)
@@ -306,14 +314,18 @@ def test_hip_graph_replay_equals_eager():
                 assert torch.equal(getattr(bufs, n), want[n]), (name, rep, n)
 
 
-def test_one_call_equals_two_calls():
+def test_one_call_equals_two_calls(oracle):
     """flowmm_plan_merge against flowmm_plan + flowmm_merge: the same decisions up to the last bits of
     the importances (the two spread the key tiles over their waves differently), and bit-identical
-    merged rows wherever the decisions are the same (both merge alike)."""
+    merged rows wherever the decisions are the same (both merge alike); where the decisions differ,
+    each side's choice must lie inside the oracle's margin band (check_layer)."""
     for theta in (0.25, 2.0):
         w = small("onecall", Hq=4, Hkv=2, spans=((35, 576, 64),), pct=(10,), n_layers=3, theta=theta)
         a = run_gpu(w)
         b = run_gpu(w, fused=True)
+        for l in range(w.n_layers):
+            check_layer(oracle, w, a, l)
+            check_layer(oracle, w, b, l)
         assert np.allclose(a["importance"], b["importance"], rtol=1e-5, atol=0)
         assert (a["mode"] == b["mode"]).all() and np.allclose(a["rho"], b["rho"], rtol=1e-5, atol=0)
         agree = (a["assign"] == b["assign"]).mean()
@@ -412,24 +424,8 @@ def test_ragged_batch_equals_each_sequence_alone():
         assert np.allclose(alone["rho"][:, 0], full["rho"][:, b], rtol=1e-5, atol=0)
 
 
-@pytest.mark.parametrize("cfg,n_layers,sample,fused", [
-    (1, 32, [(0, [0, 17]), (31, [5])], True),   # the benchmark configuration, full depth, as bench.py runs it
-    (1, 32, [(0, [0, 17]), (31, [5])], False),  # the same through the two calls (unit-resident kernels)
-    (2, 2, [(1, [0, 3])], False),
-    (3, 2, [(0, [2])], False),
-    (4, 2, [(1, [1])], False),
-    (2, 2, [(0, [1])], True),
-])
-def test_benchmark_configs_sampled_units(oracle, cfg, n_layers, sample, fused):
-    w = wl.config(cfg, n_layers=n_layers)
-    print(f"config {cfg}: {w.name} layers={n_layers} T={w.total_tokens} fused={fused}", flush=True)
-    gpu = run_gpu(w, fused=fused)
-    rep = Report()
-    for layer, heads in sample:
-        seqs = None if w.batch == 1 else [0, w.batch - 1]
-        check_layer(oracle, w, gpu, layer, kv_heads=heads, seqs=seqs, report=rep)
-        print(f"  layer {layer} heads {heads}: {rep}", flush=True)
-    # properties that hold at any size, over the whole result
+def _whole_result_invariants(w, gpu):
+    """Properties that hold at any size, over every layer, head and sequence of a result."""
     cu, cuk = w.cu_seqlens, w.cu_kept
     for b in range(w.batch):
         L, B = w.seqlens[b], w.budgets[b]
@@ -437,8 +433,122 @@ def test_benchmark_configs_sampled_units(oracle, cfg, n_layers, sample, fused):
         assert np.abs(imp.sum(axis=-1) - 1.0).max() < 1e-3
         kept = gpu["kept_idx"][:, :, cuk[b]:cuk[b + 1]]
         assert (np.diff(kept, axis=-1) > 0).all() and kept.min() >= 0 and kept.max() < L
+        assert (kept[:, :, B - w.window:] == np.arange(L - w.window, L)).all(), "a proxy token was evicted"
         asg = gpu["assign"][:, :, cu[b]:cu[b + 1]]
         assert ((asg >= -1) & (asg < B)).all()
         own = np.take_along_axis(asg, kept, axis=-1)
         assert (own == np.arange(B)).all()
         assert ((asg == -1).sum(axis=-1) == gpu["n_dropped"][:, :, b]).all()
+        assert np.isfinite(gpu["K_out"][:, :, cuk[b]:cuk[b + 1]]).all() and np.isfinite(gpu["V_out"][:, :, cuk[b]:cuk[b + 1]]).all()
+
+
+# (layer, kv heads) samples: the first, a middle and the last layer, two kv heads each
+FULL_DEPTH = {
+    1: dict(sample=[(0, [0, 17]), (15, [9, 31]), (31, [5, 22])], seqs=None),
+    2: dict(sample=[(0, [0, 3]), (13, [1, 2]), (27, [0, 2])], seqs=None),
+    3: dict(sample=[(0, [2, 7]), (16, [0, 5]), (31, [3, 6])], seqs=None),
+    4: dict(sample=[(0, [1, 2]), (14, [0, 3]), (27, [1, 3])], seqs="ends"),
+}
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_benchmark_configs_full_depth_sampled_units(oracle, cfg):
+    """The benchmark configurations at their full depth, through flowmm_plan_merge as bench.py runs them:
+    sampled (layer, kv head) units against the oracle one by one, properties of the whole result.
+    Run twice on the same cache: with the default theta (0.25 selects the cross-modal strategy on these
+    inputs) and with theta = 2, which forces the intra-modal one, so the class-split match and the two
+    pivot lists per unit are compared at full size too.  Config 4 checks both ends of the batch and its
+    shortest and longest sequence."""
+    w = wl.config(cfg)
+    spec = FULL_DEPTH[cfg]
+    tensors = upload(w)
+    seqs = None
+    if spec["seqs"] == "ends":
+        seqs = sorted({0, w.batch - 1, int(np.argmin(w.seqlens)), int(np.argmax(w.seqlens))})
+    for theta in (None, 2.0):
+        print(f"config {cfg}: {w.name} layers={w.n_layers} T={w.total_tokens} theta={theta}", flush=True)
+        gpu = run_gpu(w, theta=theta, tensors=tensors, fused=True)
+        assert (gpu["mode"] == (0 if theta is not None else 1)).all()
+        rep = Report()
+        for layer, heads in spec["sample"]:
+            check_layer(oracle, w, gpu, layer, theta=theta, kv_heads=heads, seqs=seqs, report=rep)
+            print(f"  layer {layer} heads {heads} seqs {seqs}: {rep}", flush=True)
+        _whole_result_invariants(w, gpu)
+
+
+def test_config1_two_calls_full_depth(oracle):
+    """The short-prompt configuration through flowmm_plan + flowmm_merge (three unit-resident launches)."""
+    w = wl.config(1)
+    gpu = run_gpu(w, fused=False)
+    rep = Report()
+    for layer, heads in [(0, [0, 17]), (31, [5])]:
+        check_layer(oracle, w, gpu, layer, kv_heads=heads, report=rep)
+    print(rep, flush=True)
+    _whole_result_invariants(w, gpu)
+
+
+def _planted_edge_rows(w, layer):
+    """Layer tensors of `w` with the degenerate rows the method has to cope with planted into K:
+    zero-norm keys among the evicted tokens and among the pivots (the proxy tokens are always pivots),
+    evicted keys that are exact positive multiples of a pivot's key (cosine 1), pivots with identical
+    keys (every token that prefers them sees an exact tie), evicted duplicates of each other, and an
+    image-span key that is a multiple of a text pivot (eligible only in a cross-modal layer)."""
+    K, V, Q = (x.copy() for x in w.layer_tensors(layer))
+    L = w.seqlens[0]
+    piv_a, piv_b, piv_dup, piv_zero = L - 5, L - 9, L - 12, L - 3
+    K[:, piv_zero] = 0.0                      # zero-norm pivot
+    K[:, piv_dup] = K[:, piv_b]               # two pivots with the same key
+    K[:, 60] = 0.0                            # zero-norm keys in the body (image span)
+    K[:, 61] = 0.0
+    K[:, 10] = 0.0                            # ... and in the leading text span
+    for i in (70, 150, 333):                  # image-span tokens: multiples of a text pivot
+        K[:, i] = 0.5 * K[:, piv_a]
+    for i in (5, 20):                         # text tokens: multiples of a text pivot
+        K[:, i] = 0.25 * K[:, piv_a]
+    for i in (15, 90, 200):                   # exact ties between the two identical pivots
+        K[:, i] = 0.5 * K[:, piv_b]
+    K[:, 101] = K[:, 100]                     # duplicated body keys (equal importances, equal matches)
+    K[:, 103] = K[:, 100]
+    return K, V, Q, dict(piv_a=piv_a, piv_b=piv_b, piv_dup=piv_dup, piv_zero=piv_zero)
+
+
+@pytest.mark.parametrize("theta", [-1.0, 2.0], ids=["cross", "intra"])
+@pytest.mark.parametrize("path", ["auto", "generic", "fused"])
+def test_planted_zero_rows_multiples_and_ties(oracle, path, theta):
+    import torch
+    w = small("edge_rows", Hq=4, Hkv=2, W=32, spans=((40, 560, 100),), pct=(15,), n_layers=2, theta=theta)
+    L, B = w.seqlens[0], w.budgets[0]
+    host = [_planted_edge_rows(w, l) for l in range(w.n_layers)]
+    tdt = torch.bfloat16
+    K, V, Q = (torch.stack([torch.from_numpy(h[i]) for h in host]).to("cuda:0").to(tdt) for i in range(3))
+    gpu = run_gpu(w, tensors=(K, V, Q), flags=1 if path == "generic" else 0, fused=path == "fused")
+    rep = Report()
+    for l in range(w.n_layers):
+        Kl, Vl, Ql, where = host[l]
+        check_layer(oracle, w, gpu, l, report=rep, tensors_np=(Kl, Vl, Ql))
+        for g in range(w.n_kv_heads):
+            kept, asg = gpu["kept_idx"][l][g], gpu["assign"][l][g]
+            slot = {int(t): s for s, t in enumerate(kept)}
+            is_kept = np.zeros(L, dtype=bool)
+            is_kept[kept] = True
+            # the planted roles did come out as planned (otherwise the case would test nothing)
+            assert not is_kept[[60, 61, 10]].any(), "a zero-norm body key became a pivot"
+            assert not is_kept[[5, 20, 15, 90, 200]].any()
+            # a multiple of an eligible pivot goes to that pivot (text tokens in both strategies,
+            # image-span tokens only when the layer merges across modalities)
+            for i in (5, 20):
+                assert asg[i] == slot[where["piv_a"]]
+            for i in (70, 150, 333):
+                if not is_kept[i] and theta < 0:
+                    assert asg[i] == slot[where["piv_a"]]
+                if not is_kept[i] and theta > 1:
+                    assert asg[i] == -1 or w.modality(0)[kept[asg[i]]] == 1
+            # an exact tie between identical pivots: either is right (the oracle takes the lower slot)
+            for i in (15,):
+                assert asg[i] in (slot[where["piv_b"]], slot[where["piv_dup"]])
+            # duplicated evicted keys match alike
+            if not is_kept[[100, 101, 103]].any():
+                assert asg[100] == asg[101] == asg[103]
+            # a zero-norm evicted key has cosine 0 with every pivot: any eligible slot is a tie; it must not be dropped
+            assert asg[10] >= 0
+    print(rep, flush=True)
