@@ -141,6 +141,22 @@ flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K, const voi
                                 const flowmm_plan_buffers *plan, void *K_out, void *V_out, void *workspace,
                                 size_t workspace_bytes, void *stream);
 
+/* flowmm_plan_merge for callers that cannot allocate device memory for a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * rules as flowmm_plan_merge, minus the workspace: the scratch lives in a device array that is part
+ * of the library itself (flowmm_static_workspace_bytes() bytes, 64 MiB; every GPU the library runs
+ * on holds it from the first use until the process ends).  The call makes no hipMalloc / hipFree and
+ * calls no allocating library routine; inputs, plan buffers and outputs are still the caller's.
+ * Shapes whose flowmm_plan_sizes workspace exceeds the array return FLOWMM_EWORKSPACE (nothing is
+ * enqueued; the message gives both sizes).  All calls on one GPU share that GPU's array: calls that
+ * overlap on one GPU (different streams without ordering, or different host threads) race; order them.
+ * The kernels initialise every word of scratch they read, so what an earlier call left there does
+ * not matter.  The first call on a device looks up the array's address on that device (which loads
+ * the library's code there): make one call before capturing into a graph. */
+size_t flowmm_static_workspace_bytes(void);
+flowmm_status flowmm_plan_merge_static(const flowmm_params *p, const void *K, const void *V, const void *Q_window,
+                                       const flowmm_plan_buffers *plan, void *K_out, void *V_out, void *stream);
+
 /* The cross-modal interaction ratio with EVERY token of the prompt as a query: the rho^l equation
  * of the paper (Information Flow Guided Merging) evaluated literally over the causal prefill
  * attention, instead of the estimate from the last `window` queries that flowmm_plan uses.

@@ -19,7 +19,8 @@ FLOWMM_F32, FLOWMM_BF16 = 0, 1
 FLOWMM_FLAG_GENERIC_PATH, FLOWMM_FLAG_INVERT_FLOW, FLOWMM_FLAG_WEIGHTED_MERGE = 1, 2, 4
 STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWORKSPACE", "FLOWMM_EHIP"]
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
-EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_flow_exact",
+EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_plan_merge_static",
+           "flowmm_static_workspace_bytes", "flowmm_flow_exact",
            "flowmm_decode_attention", "flowmm_last_error",
            "flowmm_profile_kernel_count", "flowmm_profile_kernel_name", "flowmm_profile_select",
            "flowmm_profile_collect")
@@ -58,9 +59,17 @@ _lib = None
 
 
 def load(build_if_missing: bool = True):
-    """Load libflowmm.so; it is built first only if no library is there at all."""
+    """Load libflowmm.so; it is built first only if no library is there at all.
+
+    PyTorch wheels carry a HIP runtime of their own.  Whichever of the two libraries is loaded first
+    decides which runtime the process gets, and a process that ends up with two of them has one that
+    sees no device.  Callers here always hand over PyTorch tensors, so PyTorch goes first when it is there."""
     global _lib
     if _lib is None:
+        try:
+            import torch  # noqa: F401  (only for its HIP runtime; see above)
+        except ImportError:
+            pass
         path = _build.library_path()
         if not os.path.exists(path):
             if not build_if_missing:
@@ -76,6 +85,11 @@ def load(build_if_missing: bool = True):
         lib.flowmm_plan_merge.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+        lib.flowmm_plan_merge_static.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.flowmm_plan_merge_static.restype = C.c_int
+        lib.flowmm_static_workspace_bytes.argtypes = []
+        lib.flowmm_static_workspace_bytes.restype = C.c_size_t
         lib.flowmm_flow_exact.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                           C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.flowmm_flow_exact.restype = C.c_int
@@ -175,6 +189,18 @@ def flowmm_plan_merge(params: Params, K: int, V: int, Q_window: int, plan_ptrs: 
                                     C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
+def flowmm_plan_merge_static(params: Params, K: int, V: int, Q_window: int, plan_ptrs: Sequence[int], K_out: int,
+                             V_out: int, stream: int = 0):
+    """flowmm_plan_merge on the library's own scratch array (no workspace argument)."""
+    pb = _plan_struct(plan_ptrs)
+    _check(load().flowmm_plan_merge_static(C.byref(params.c), C.c_void_p(K), C.c_void_p(V), C.c_void_p(Q_window),
+                                           C.byref(pb), C.c_void_p(K_out), C.c_void_p(V_out), C.c_void_p(stream)))
+
+
+def flowmm_static_workspace_bytes() -> int:
+    return int(load().flowmm_static_workspace_bytes())
+
+
 def flowmm_flow_exact(params: Params, K: int, Q_full: int, q_strides: Tuple[int, int, int], rho: int, mode: int,
                       workspace: int, workspace_bytes: int, stream: int = 0):
     _check(load().flowmm_flow_exact(C.byref(params.c), C.c_void_p(K), C.c_void_p(Q_full), *[C.c_int64(int(x)) for x in q_strides],
@@ -253,6 +279,10 @@ class DeviceBuffers:
         flowmm_plan_merge(self.params, K.data_ptr(), V.data_ptr(), Q.data_ptr(), self.plan_ptrs,
                           self.K_out.data_ptr(), self.V_out.data_ptr(), self.workspace.data_ptr(),
                           self.workspace_bytes, stream)
+
+    def plan_merge_static(self, K, V, Q, stream: int = 0):
+        flowmm_plan_merge_static(self.params, K.data_ptr(), V.data_ptr(), Q.data_ptr(), self.plan_ptrs,
+                                 self.K_out.data_ptr(), self.V_out.data_ptr(), stream)
 
     def flow_exact(self, K, Q_full, stream: int = 0):
         """Q_full [Lyr][Hq][T][d] contiguous; fills self.rho and self.mode."""

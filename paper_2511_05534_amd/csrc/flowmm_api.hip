@@ -2,6 +2,7 @@
 // kernel sequencing.  All arithmetic of the method runs in the kernels this file launches.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -351,6 +352,62 @@ flowmm_status check_merge_args(const Layout &lo, const void *K, const void *V, v
   return FLOWMM_OK;
 }
 
+
+// ---- the whole method in one enqueue, on a workspace that has already been found large enough ----
+flowmm_status check_plan_merge_args(const Layout &lo, const void *K, const void *V, const void *Q_window,
+                                    const flowmm_plan_buffers *plan, void *K_out, void *V_out) {
+  flowmm_status st;
+  if (!Q_window) return fail(FLOWMM_EINVAL, "Q_window must not be NULL");
+  if (misaligned(Q_window)) return fail(FLOWMM_EINVAL, "Q_window must be 16-byte aligned");
+  if ((st = check_merge_args(lo, K, V, K_out, V_out)) != FLOWMM_OK) return st;
+  return check_plan_buffers(plan);
+}
+
+flowmm_status plan_merge_in(const Layout &lo, const void *K, const void *V, const void *Q_window,
+                            const flowmm_plan_buffers *plan, void *K_out, void *V_out, void *workspace, void *stream) {
+  Ctx c;
+  fill_ctx(c, lo, plan, workspace, stream);
+  c.K = K; c.V = V; c.Q = Q_window; c.K_out = K_out; c.V_out = V_out;
+  hipError_t e;
+  if (c.sh.unit_path) {
+    if ((e = launch_unit_plan(c, false)) != hipSuccess) return hip_fail(e, "unit-resident plan kernel");
+    if ((e = launch_unit_merge(c, true)) != hipSuccess) return hip_fail(e, "unit-resident flow and merge kernel");
+    return FLOWMM_OK;
+  }
+  // the metadata block sits in front of the scratch that the plan and the merge kernels share, so one upload serves both
+  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
+  if ((e = launch_score(c)) != hipSuccess) return hip_fail(e, "score kernels");
+  if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
+  if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
+  if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
+  return FLOWMM_OK;
+}
+
+// ---- scratch for callers that cannot allocate ------------------------------------------------------
+// Device memory the library itself owns: every GPU it runs on holds this array from the first use
+// until the process ends.  Host code never uses the array's name as an address: the name is a
+// host-side stand-in, and each device has its own copy at its own address, looked up once per
+// device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+flowmm_status static_scratch(void **out) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void *> ptr_of[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(FLOWMM_EUNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxDevices - 1);
+  void *ptr = ptr_of[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if ((e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255)) return fail(FLOWMM_EHIP, "the scratch array has no usable device address");
+    ptr_of[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return FLOWMM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -385,28 +442,31 @@ FLOWMM_API flowmm_status flowmm_plan_merge(const flowmm_params *p, const void *K
   Layout lo;
   flowmm_status st = build_layout(p, lo);
   if (st != FLOWMM_OK) return st;
-  if (!Q_window || !workspace) return fail(FLOWMM_EINVAL, "Q_window and workspace must not be NULL");
-  if (misaligned(Q_window) || misaligned(workspace)) return fail(FLOWMM_EINVAL, "Q_window and workspace must be 16-byte aligned");
-  if ((st = check_merge_args(lo, K, V, K_out, V_out)) != FLOWMM_OK) return st;
-  if ((st = check_plan_buffers(plan)) != FLOWMM_OK) return st;
+  if (!workspace) return fail(FLOWMM_EINVAL, "workspace must not be NULL");
+  if (misaligned(workspace)) return fail(FLOWMM_EINVAL, "workspace must be 16-byte aligned");
+  if ((st = check_plan_merge_args(lo, K, V, Q_window, plan, K_out, V_out)) != FLOWMM_OK) return st;
   if (workspace_bytes < lo.workspace_bytes)
     return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.workspace_bytes);
-  Ctx c;
-  fill_ctx(c, lo, plan, workspace, stream);
-  c.K = K; c.V = V; c.Q = Q_window; c.K_out = K_out; c.V_out = V_out;
-  hipError_t e;
-  if (c.sh.unit_path) {
-    if ((e = launch_unit_plan(c, false)) != hipSuccess) return hip_fail(e, "unit-resident plan kernel");
-    if ((e = launch_unit_merge(c, true)) != hipSuccess) return hip_fail(e, "unit-resident flow and merge kernel");
-    return FLOWMM_OK;
-  }
-  // the metadata block sits in front of the scratch that the plan and the merge kernels share, so one upload serves both
-  if ((e = launch_meta_upload(c, lo.words.data(), (int)lo.words.size(), true)) != hipSuccess) return hip_fail(e, "metadata upload");
-  if ((e = launch_score(c)) != hipSuccess) return hip_fail(e, "score kernels");
-  if ((e = launch_select(c)) != hipSuccess) return hip_fail(e, "select kernel");
-  if ((e = launch_match(c)) != hipSuccess) return hip_fail(e, "match kernel");
-  if ((e = launch_merge(c)) != hipSuccess) return hip_fail(e, "merge kernels");
-  return FLOWMM_OK;
+  return plan_merge_in(lo, K, V, Q_window, plan, K_out, V_out, workspace, stream);
+}
+
+FLOWMM_API size_t flowmm_static_workspace_bytes(void) { return kStaticScratchBytes; }
+
+FLOWMM_API flowmm_status flowmm_plan_merge_static(const flowmm_params *p, const void *K, const void *V,
+                                       const void *Q_window, const flowmm_plan_buffers *plan, void *K_out,
+                                       void *V_out, void *stream) {
+  Layout lo;
+  flowmm_status st = build_layout(p, lo);
+  if (st != FLOWMM_OK) return st;
+  if (lo.workspace_bytes > kStaticScratchBytes)
+    return fail(FLOWMM_EWORKSPACE,
+                "these shapes need %zu bytes of scratch, the library's own scratch array holds %zu: "
+                "use flowmm_plan_merge with a workspace of the caller's",
+                lo.workspace_bytes, kStaticScratchBytes);
+  if ((st = check_plan_merge_args(lo, K, V, Q_window, plan, K_out, V_out)) != FLOWMM_OK) return st;
+  void *ws = nullptr;
+  if ((st = static_scratch(&ws)) != FLOWMM_OK) return st;  // the first HIP call: everything above is host-only
+  return plan_merge_in(lo, K, V, Q_window, plan, K_out, V_out, ws, stream);
 }
 
 FLOWMM_API flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K, const void *Q_full,

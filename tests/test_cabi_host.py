@@ -105,6 +105,9 @@ def test_pointer_checks_happen_before_any_launch():
         (lambda: fb.flowmm_plan_merge(p, good, far[0], far[3], plan, far[1], far[1] + 256, good, ws), "overlap"),
         (lambda: fb.flowmm_plan_merge(p, good, far[0], far[3], [good, good, good, 0, good, good], far[1], far[2], good, ws),
          "plan->kept_idx"),
+        (lambda: fb.flowmm_plan_merge_static(p, good, far[0], 0, plan, far[1], far[2]), "NULL"),
+        (lambda: fb.flowmm_plan_merge_static(p, good, far[0], far[3], plan, far[1], far[1] + 256), "overlap"),
+        (lambda: fb.flowmm_plan_merge_static(p, good + 8, far[0], far[3], plan, far[1], far[2]), "aligned"),
         (lambda: fb.flowmm_flow_exact(p, good, 0, qs, good, good, good, ws), "NULL"),
         (lambda: fb.flowmm_flow_exact(p, good, far[0], qs, good + 2, good, good, ws), "4-byte"),
         (lambda: fb.flowmm_flow_exact(p, good, far[0], (qs[0], qs[1], 100), good, good, good, ws), "stride"),
@@ -141,3 +144,21 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit():
+    """flowmm_plan_merge_static works on a 64 MiB array inside the library: shapes that need more are
+    refused on the host, with both sizes in the message, before any HIP call."""
+    cap = fb.flowmm_static_workspace_bytes()
+    assert cap == 64 << 20
+    far = [1 << 40, 1 << 41, 1 << 42, 1 << 43, 1 << 44]
+    plan = [0x10000] * 6
+    for i, fits in ((1, True), (2, True), (3, False), (4, False)):
+        p = fb.Params.from_workload(wl.config(i))
+        _, ws = fb.flowmm_plan_sizes(p)
+        assert (ws <= cap) == fits
+        if not fits:
+            with pytest.raises(fb.FlowMMError) as ei:
+                fb.flowmm_plan_merge_static(p, far[0], far[1], far[2], plan, far[3], far[4])
+            assert ei.value.status == fb.FLOWMM_EWORKSPACE
+            assert str(ws) in ei.value.message and str(cap) in ei.value.message
