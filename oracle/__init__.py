@@ -5,4 +5,5 @@ package; the product path never does.
 """
 from .flowmm_oracle import (  # noqa: F401
     build, score, flow, select, match, merge, merge_weighted, decode_attention, round_output, layer_pass, num_threads,
+    cache_append, cache_remerge,
 )

@@ -35,6 +35,12 @@
  *   fmo_decode_attention      - one decode step of attention (the attention-output equation of
  *                the Preliminary section, o_t = softmax(q_t K^T / sqrt d) V) over a compacted cache:
  *                what the paper's decoding-latency table exercises on the compressed cache.
+ *   fmo_cache_append          - the cache-append equation of the Preliminary section,
+ *                K_t = [K_{t-1}, k_t], V_t = [V_{t-1}, v_t], on a cache with head room per sequence.
+ *   fmo_cache_remerge         - this build's reading of what the paper leaves open (what to do when
+ *                the compressed cache has outgrown its budget during decoding): the stages above run
+ *                again on the valid rows of the cache as if they were a prompt of one modality, the
+ *                last W rows being the proxies; the merged rows replace the head of the cache.
  *   ("Without sensitivity-adaptive matching" is tau = +inf; "without information flow
  *   guidance" is a theta below 0 or above 1; neither needs code of its own.)
  */
@@ -327,4 +333,45 @@ void fmo_layer(int Hq, int Hkv, int L, int W, int d, int B, int dtype, double sc
     free(vo);
     free(nm);
   }
+}
+
+/* Cache-append equation (Preliminary): the new token's key and value become row `length` of every
+ * kv head's cache.  Kc, Vc [Hkv][capacity][d]; k, v [Hkv][d].  Returns the new length, or -1 if full. */
+int fmo_cache_append(int Hkv, int capacity, int d, int length, float *Kc, float *Vc, const float *k,
+                     const float *v) {
+  if (length < 0 || length >= capacity) return -1;
+  for (int g = 0; g < Hkv; ++g)
+    for (int c = 0; c < d; ++c) {
+      Kc[((size_t)g * capacity + length) * d + c] = k[(size_t)g * d + c];
+      Vc[((size_t)g * capacity + length) * d + c] = v[(size_t)g * d + c];
+    }
+  return length + 1;
+}
+
+/* Re-merge of one sequence's cache in one layer (reading of this build, the paper gives no policy):
+ * the n valid rows are a prompt whose tokens all share one modality, the last W rows are the proxies
+ * (Q [Hq][W][d] are their queries); score, flow, select, match and merge run as for a prompt, and the
+ * B merged rows, rounded to the cache dtype, replace rows [0, B).  Rows from B on are left as they
+ * were (stale).  Kc, Vc [Hkv][capacity][d].  Outputs as fmo_layer's, for n tokens.  Returns B. */
+int fmo_cache_remerge(int Hq, int Hkv, int capacity, int n, int W, int d, int B, int dtype, double scale,
+                      double tau, float *Kc, float *Vc, const float *Q, double *I, double *rho,
+                      int32_t *mode, int32_t *kept_idx, int32_t *assign, int32_t *n_dropped) {
+  float *K = (float *)malloc(sizeof(float) * (size_t)Hkv * n * d);
+  float *V = (float *)malloc(sizeof(float) * (size_t)Hkv * n * d);
+  float *Ko = (float *)malloc(sizeof(float) * (size_t)Hkv * B * d);
+  float *Vo = (float *)malloc(sizeof(float) * (size_t)Hkv * B * d);
+  int32_t *mod = (int32_t *)calloc((size_t)n, sizeof(int32_t)); /* one modality for every row */
+  for (int g = 0; g < Hkv; ++g) {
+    memcpy(K + (size_t)g * n * d, Kc + (size_t)g * capacity * d, sizeof(float) * (size_t)n * d);
+    memcpy(V + (size_t)g * n * d, Vc + (size_t)g * capacity * d, sizeof(float) * (size_t)n * d);
+  }
+  /* with one modality rho is 0 and either strategy admits the same pivots; theta plays no part */
+  fmo_layer(Hq, Hkv, n, W, d, B, dtype, scale, -1.0, tau, K, V, Q, mod, I, rho, mode, kept_idx, assign,
+            n_dropped, Ko, Vo);
+  for (int g = 0; g < Hkv; ++g) {
+    memcpy(Kc + (size_t)g * capacity * d, Ko + (size_t)g * B * d, sizeof(float) * (size_t)B * d);
+    memcpy(Vc + (size_t)g * capacity * d, Vo + (size_t)g * B * d, sizeof(float) * (size_t)B * d);
+  }
+  free(K); free(V); free(Ko); free(Vo); free(mod);
+  return B;
 }

@@ -38,6 +38,8 @@ def _load():
         _lib.fmo_flow.restype = C.c_int
         _lib.fmo_match.restype = C.c_int
         _lib.fmo_num_threads.restype = C.c_int
+        _lib.fmo_cache_append.restype = C.c_int
+        _lib.fmo_cache_remerge.restype = C.c_int
     return _lib
 
 
@@ -179,3 +181,36 @@ def layer_pass(K, V, Q, mod, B, dtype: str, theta: float, tau: float, scale=None
                       _p(ko, C.c_float), _p(vo, C.c_float))
     return dict(I=I, rho=float(rho.value), mode=int(mode.value), kept_idx=kept, assign=assign,
                 n_dropped=nd, K_out=ko, V_out=vo)
+
+
+def cache_append(Kc, Vc, length: int, k, v) -> int:
+    """Cache-append equation on Kc, Vc [Hkv][capacity][d] (float32, contiguous, modified in place):
+    row `length` of every kv head becomes k, v [Hkv][d].  Returns the new length, or -1 if the cache is full."""
+    assert Kc.dtype == np.float32 and Vc.dtype == np.float32 and Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    k, v = _f32(k), _f32(v)
+    Hkv, cap, d = Kc.shape
+    return int(_load().fmo_cache_append(Hkv, cap, d, int(length), _p(Kc, C.c_float), _p(Vc, C.c_float),
+                                        _p(k, C.c_float), _p(v, C.c_float)))
+
+
+def cache_remerge(Kc, Vc, n: int, Q, B: int, dtype: str, tau: float, scale=None):
+    """Re-merge of the first n rows of Kc, Vc [Hkv][capacity][d] (float32, contiguous, modified in place:
+    rows [0, B) become the merged rows) with Q [Hq][W][d] the queries of the last W valid rows.
+    Returns the plan of the re-merge (as layer_pass does, without the output rows) and the new length."""
+    assert Kc.dtype == np.float32 and Vc.dtype == np.float32 and Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    Q = _f32(Q)
+    Hkv, cap, d = Kc.shape
+    Hq, W, _ = Q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    I = np.empty((Hkv, n), dtype=np.float64)
+    rho = C.c_double(0.0)
+    mode = C.c_int32(0)
+    kept = np.empty((Hkv, B), dtype=np.int32)
+    assign = np.empty((Hkv, n), dtype=np.int32)
+    nd = np.empty(Hkv, dtype=np.int32)
+    new_len = _load().fmo_cache_remerge(Hq, Hkv, cap, int(n), W, d, int(B), 1 if dtype == "bf16" else 0,
+                                        C.c_double(scale), C.c_double(tau), _p(Kc, C.c_float), _p(Vc, C.c_float),
+                                        _p(Q, C.c_float), _p(I, C.c_double), C.byref(rho), C.byref(mode),
+                                        _p(kept, C.c_int32), _p(assign, C.c_int32), _p(nd, C.c_int32))
+    return dict(I=I, rho=float(rho.value), mode=int(mode.value), kept_idx=kept, assign=assign, n_dropped=nd), int(new_len)

@@ -508,6 +508,122 @@ def test_weighted_merge_special_cases(oracle):
 
 
 # --------------------------------------------------------------------------------------
+# decode-time maintenance: cache append and re-merge
+# --------------------------------------------------------------------------------------
+def test_cache_append_is_concatenation(oracle):
+    """K_t = [K_{t-1}, k_t], V_t = [V_{t-1}, v_t] (Preliminary): after t appends the valid rows are
+    the appended tokens in order, the rows behind them are untouched, and a full cache refuses."""
+    rng = np.random.default_rng(5)
+    Hkv, cap, d = 3, 6, 8
+    Kc = np.full((Hkv, cap, d), -7.0, dtype=np.float32)
+    Vc = np.full((Hkv, cap, d), -9.0, dtype=np.float32)
+    toks = [(rng.standard_normal((Hkv, d)).astype(np.float32), rng.standard_normal((Hkv, d)).astype(np.float32))
+            for _ in range(cap)]
+    n = 0
+    for t, (k, v) in enumerate(toks):
+        n = oracle.cache_append(Kc, Vc, n, k, v)
+        assert n == t + 1
+        want_k = np.concatenate([x[0][:, None, :] for x in toks[:n]], axis=1)
+        want_v = np.concatenate([x[1][:, None, :] for x in toks[:n]], axis=1)
+        assert (Kc[:, :n] == want_k).all() and (Vc[:, :n] == want_v).all()
+        assert (Kc[:, n:] == -7.0).all() and (Vc[:, n:] == -9.0).all()
+    before = Kc.copy()
+    assert oracle.cache_append(Kc, Vc, n, toks[0][0], toks[0][1]) == -1 and (Kc == before).all()
+
+
+def _cache_case(seed, Hq=4, Hkv=2, cap=40, n=33, W=4, d=8):
+    rng = np.random.default_rng(seed)
+    Kc = rng.standard_normal((Hkv, cap, d)).astype(np.float32)
+    Vc = rng.standard_normal((Hkv, cap, d)).astype(np.float32)
+    Q = rng.standard_normal((Hq, W, d)).astype(np.float32)
+    return Kc, Vc, Q
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_cache_remerge_is_the_method_on_the_cache_rows(oracle, seed):
+    """The re-merge against the dense numpy restatements of every stage, run on the valid rows as a
+    prompt of one modality: dense causal softmax -> stable argsort -> masked cosine argmax -> scatter mean."""
+    Kc, Vc, Q = _cache_case(seed)
+    Hkv, cap, d = Kc.shape
+    n, W, B = 33, 4, 11
+    K0, V0 = Kc.copy(), Vc.copy()
+    tau = 0.09
+    plan, new_len = oracle.cache_remerge(Kc, Vc, n, Q, B, "f32", tau)
+    assert new_len == B and plan["rho"] == 0.0
+    mod = np.zeros(n, dtype=np.int32)
+    I_np, _ = np_score(K0[:, :n], Q, mod, 1.0 / np.sqrt(d))
+    np.testing.assert_allclose(plan["I"], I_np, rtol=1e-12, atol=1e-300)
+    for g in range(Hkv):
+        kept = np_select(plan["I"][g], W, B)
+        assert plan["kept_idx"][g].tolist() == kept.tolist()
+        a = np_match(K0[g, :n], plan["I"][g], kept, mod, 1, tau)
+        assert plan["assign"][g].tolist() == a.tolist()
+        assert plan["n_dropped"][g] == int((a == -1).sum())
+        ko, vo, _ = np_merge(K0[g, :n], V0[g, :n], kept, a)
+        np.testing.assert_allclose(Kc[g, :B], ko.astype(np.float32), rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(Vc[g, :B], vo.astype(np.float32), rtol=1e-6, atol=1e-7)
+    # rows behind the new length are left alone
+    assert (Kc[:, B:] == K0[:, B:]).all() and (Vc[:, B:] == V0[:, B:]).all()
+
+
+def test_cache_remerge_special_cases(oracle):
+    Kc, Vc, Q = _cache_case(9)
+    K0, V0 = Kc.copy(), Vc.copy()
+    n, W = 33, 4
+    # budget = length: nothing is evicted, the cache is unchanged bit for bit
+    plan, new_len = oracle.cache_remerge(Kc, Vc, n, Q, n, "f32", 0.5)
+    assert new_len == n and (Kc == K0).all() and (Vc == V0).all()
+    assert plan["kept_idx"][0].tolist() == list(range(n))
+    # every pivot gated out: pure eviction, the kept rows move up unchanged; the proxies are always kept
+    plan, _ = oracle.cache_remerge(Kc, Vc, n, Q, 10, "f32", -1.0)
+    for g in range(Kc.shape[0]):
+        kept = plan["kept_idx"][g]
+        assert (Kc[g, :10] == K0[g, kept]).all() and (Vc[g, :10] == V0[g, kept]).all()
+        assert kept[-W:].tolist() == list(range(n - W, n))
+        assert plan["n_dropped"][g] == n - 10
+    # it equals the whole-prompt pass on the same rows with one modality, whatever theta says
+    Kc, Vc = K0.copy(), V0.copy()
+    plan, _ = oracle.cache_remerge(Kc, Vc, n, Q, 12, "bf16", 0.08)
+    for theta in (-1.0, 0.25, 2.0):
+        ref = oracle.layer_pass(K0[:, :n], V0[:, :n], Q, np.zeros(n, dtype=np.int32), 12, "bf16", theta, 0.08)
+        assert (ref["assign"] == plan["assign"]).all() and (ref["kept_idx"] == plan["kept_idx"]).all()
+        assert (ref["K_out"] == Kc[:, :12]).all() and (ref["V_out"] == Vc[:, :12]).all()
+    # mass conservation of the fold (fp32 rounding only): sum over slots of (1 + members) * row + dropped rows
+    Kc, Vc = K0.copy(), V0.copy()
+    plan, _ = oracle.cache_remerge(Kc, Vc, n, Q, 9, "f32", np.inf)
+    for g in range(Kc.shape[0]):
+        cnt = np.bincount(plan["assign"][g], minlength=9).astype(np.float64)
+        total = (cnt[:, None] * Kc[g, :9].astype(np.float64)).sum(axis=0)
+        np.testing.assert_allclose(total, K0[g, :n].astype(np.float64).sum(axis=0), rtol=0, atol=1e-4)
+
+
+def test_prefill_merge_then_appends_then_remerge_keeps_the_books(oracle):
+    """The life of one cache: merged prompt rows, decoded tokens appended behind them up to capacity,
+    then a re-merge back to the budget; lengths follow B -> B + R -> B."""
+    K, V, Q, mod = rand_case(31, L=50, W=4)
+    B, R = 12, 8
+    ref = oracle.layer_pass(K, V, Q, mod, B, "f32", 0.25, 0.1)
+    Hkv, _, d = K.shape
+    Kc = np.zeros((Hkv, B + R, d), dtype=np.float32)
+    Vc = np.zeros_like(Kc)
+    Kc[:, :B], Vc[:, :B] = ref["K_out"], ref["V_out"]
+    rng = np.random.default_rng(1)
+    n = B
+    for _ in range(R):
+        n = oracle.cache_append(Kc, Vc, n, rng.standard_normal((Hkv, d)).astype(np.float32),
+                                rng.standard_normal((Hkv, d)).astype(np.float32))
+    assert n == B + R and oracle.cache_append(Kc, Vc, n, Kc[:, 0], Vc[:, 0]) == -1
+    tail = Kc[:, B + R - 4:B + R].copy()
+    plan, n = oracle.cache_remerge(Kc, Vc, n, Q, B, "f32", np.inf)
+    assert n == B
+    # the four most recent tokens are the proxies: they survive as the last four rows, unmerged-into or not
+    for g in range(Hkv):
+        assert plan["kept_idx"][g][-4:].tolist() == list(range(B + R - 4, B + R))
+        alone = np.bincount(plan["assign"][g], minlength=B)[-4:] == 1
+        assert (Kc[g, B - 4:B][alone] == tail[g][alone]).all()
+
+
+# --------------------------------------------------------------------------------------
 # decode attention over the compacted cache
 # --------------------------------------------------------------------------------------
 def test_decode_attention_matches_dense_softmax_and_closed_forms(oracle):
