@@ -185,6 +185,52 @@ flowmm_status flowmm_flow_exact(const flowmm_params *p, const void *K, const voi
 flowmm_status flowmm_decode_attention(const flowmm_params *p, const void *q, const void *K_c, const void *V_c,
                                       void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- decode-time maintenance of the compacted cache --------------------------------------------
+ * The paper's Preliminary section appends the key and value of every decoded token to the cache
+ * (K_t = [K_{t-1}, k_t], V_t = [V_{t-1}, v_t]) and says nothing about what happens once a compressed
+ * cache has grown past its budget again.  The reading built here: the cache of sequence b owns the
+ * rows [cu_capacity[b], cu_capacity[b+1]) of K_c / V_c (capacity C_b >= its budget B_b, the same
+ * range in every layer and kv head), of which the first lengths[b] are valid: the merged prompt rows,
+ * then the decoded tokens in order.  flowmm_cache_append adds one token per sequence; when a
+ * sequence's range is full the caller has flowmm_cache_remerge compress it back to B_b rows by the
+ * very method of flowmm_plan_merge, with the cache's valid rows as the "prompt" and its last
+ * `window` rows (the most recent tokens, whose queries the caller has kept) as the proxy tokens.
+ * The re-merge is blind to modality: a row merged across modalities has none, decoded tokens are all
+ * text, and the paper measures rho on prompt attention only; every row counts as one token of one
+ * modality (so rho = 0 and the strategies coincide), and a merged row weighs like any other row.
+ *
+ * In both calls p describes the cache: n_layers, n_q_heads, n_kv_heads, head_dim, dtype, batch,
+ * k_stride_* (the strides of K_c and V_c, elements), and for the re-merge budget_tokens, window,
+ * scale, tau, q_stride_* and flags (FLOWMM_FLAG_GENERIC_PATH, FLOWMM_FLAG_WEIGHTED_MERGE);
+ * cu_seqlens, spans, cu_spans and theta are not read.  cu_capacity (host, [batch+1], starts at 0,
+ * increasing) and lengths (host, [batch], 0 <= lengths[b] <= C_b) are read during the call only. */
+
+/* Cache-append equation: row cu_capacity[b] + lengths[b] of every (layer, kv head) of K_c / V_c
+ * becomes k_new / v_new [Lyr][Hkv][batch][d] (device, contiguous, dtype of the cache).  The caller
+ * then counts lengths[b] + 1.  FLOWMM_EINVAL if some sequence is full (re-merge it first); nothing
+ * is enqueued then. */
+flowmm_status flowmm_cache_append(const flowmm_params *p, const int32_t *cu_capacity, const int32_t *lengths,
+                                  void *K_c, void *V_c, const void *k_new, const void *v_new, void *stream);
+
+/* Sizes for flowmm_cache_remerge of sequence seq at the length given (at most its capacity): bytes of
+ * the six plan buffers (field order of flowmm_plan_buffers, for one sequence of that many tokens)
+ * and of the workspace (which also holds the merged rows until they are stored back). */
+flowmm_status flowmm_cache_remerge_sizes(const flowmm_params *p, const int32_t *cu_capacity, int32_t seq,
+                                         int32_t length, size_t plan_bytes[6], size_t *workspace_bytes);
+
+/* Compress the lengths[seq] valid rows of sequence seq back to budget_tokens[seq] rows: score
+ * (Q_window: the queries of the last `window` valid rows, [Lyr][Hq][window][d] through q_stride_*),
+ * select, match and merge exactly as flowmm_plan_merge does for a single-modality prompt of
+ * lengths[seq] tokens with tau[seq]; the merged rows replace rows [0, B) of the sequence's range
+ * (ascending position, as always), the rows behind them are stale, and the caller sets
+ * lengths[seq] = budget_tokens[seq].  plan receives the plan of this re-merge (positions are cache
+ * rows relative to the start of the sequence's range).  Requires window <= lengths[seq] and
+ * budget_tokens[seq] in [window, lengths[seq]]; other sequences are not touched. */
+flowmm_status flowmm_cache_remerge(const flowmm_params *p, const int32_t *cu_capacity, const int32_t *lengths,
+                                   int32_t seq, void *K_c, void *V_c, const void *Q_window,
+                                   const flowmm_plan_buffers *plan, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
 /* Message of the last failing call on this thread (static storage, never NULL). */
 const char *flowmm_last_error(void);
 

@@ -21,6 +21,7 @@ STATUS_NAMES = ["FLOWMM_OK", "FLOWMM_EINVAL", "FLOWMM_EUNSUPPORTED", "FLOWMM_EWO
 PLAN_FIELDS = ("importance", "rho", "mode", "kept_idx", "assign", "n_dropped")
 EXPORTS = ("flowmm_plan_sizes", "flowmm_plan", "flowmm_merge", "flowmm_plan_merge", "flowmm_plan_merge_static",
            "flowmm_static_workspace_bytes", "flowmm_flow_exact",
+           "flowmm_cache_append", "flowmm_cache_remerge_sizes", "flowmm_cache_remerge",
            "flowmm_decode_attention", "flowmm_last_error",
            "flowmm_profile_kernel_count", "flowmm_profile_kernel_name", "flowmm_profile_select",
            "flowmm_profile_collect")
@@ -90,6 +91,15 @@ def load(build_if_missing: bool = True):
         lib.flowmm_plan_merge_static.restype = C.c_int
         lib.flowmm_static_workspace_bytes.argtypes = []
         lib.flowmm_static_workspace_bytes.restype = C.c_size_t
+        i32p = C.POINTER(C.c_int32)
+        lib.flowmm_cache_append.argtypes = [C.POINTER(flowmm_params), i32p, i32p] + [C.c_void_p] * 5
+        lib.flowmm_cache_append.restype = C.c_int
+        lib.flowmm_cache_remerge_sizes.argtypes = [C.POINTER(flowmm_params), i32p, C.c_int32, C.c_int32,
+                                                   C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        lib.flowmm_cache_remerge_sizes.restype = C.c_int
+        lib.flowmm_cache_remerge.argtypes = [C.POINTER(flowmm_params), i32p, i32p, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.POINTER(flowmm_plan_buffers), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.flowmm_cache_remerge.restype = C.c_int
         lib.flowmm_flow_exact.argtypes = [C.POINTER(flowmm_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                           C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.flowmm_flow_exact.restype = C.c_int
@@ -199,6 +209,39 @@ def flowmm_plan_merge_static(params: Params, K: int, V: int, Q_window: int, plan
 
 def flowmm_static_workspace_bytes() -> int:
     return int(load().flowmm_static_workspace_bytes())
+
+
+def _i32_array(values):
+    a = np.asarray(values, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def flowmm_cache_append(params: Params, cu_capacity, lengths, K_c: int, V_c: int, k_new: int, v_new: int, stream: int = 0):
+    """Cache-append equation: one new K/V row per sequence behind its `lengths[b]` valid rows.
+    `params` describes the cache (its k strides are the cache's strides)."""
+    cap, cap_p = _i32_array(cu_capacity)
+    ln, ln_p = _i32_array(lengths)
+    _check(load().flowmm_cache_append(C.byref(params.c), cap_p, ln_p, C.c_void_p(K_c), C.c_void_p(V_c),
+                                      C.c_void_p(k_new), C.c_void_p(v_new), C.c_void_p(stream)))
+
+
+def flowmm_cache_remerge_sizes(params: Params, cu_capacity, seq: int, length: int):
+    cap, cap_p = _i32_array(cu_capacity)
+    sizes = (C.c_size_t * 6)()
+    ws = C.c_size_t(0)
+    _check(load().flowmm_cache_remerge_sizes(C.byref(params.c), cap_p, int(seq), int(length), sizes, C.byref(ws)))
+    return [int(x) for x in sizes], int(ws.value)
+
+
+def flowmm_cache_remerge(params: Params, cu_capacity, lengths, seq: int, K_c: int, V_c: int, Q_window: int,
+                         plan_ptrs: Sequence[int], workspace: int, workspace_bytes: int, stream: int = 0):
+    """Compress the valid rows of sequence `seq` of the cache back to its budget (rows [0, B) of its range)."""
+    cap, cap_p = _i32_array(cu_capacity)
+    ln, ln_p = _i32_array(lengths)
+    pb = _plan_struct(plan_ptrs)
+    _check(load().flowmm_cache_remerge(C.byref(params.c), cap_p, ln_p, int(seq), C.c_void_p(K_c), C.c_void_p(V_c),
+                                       C.c_void_p(Q_window), C.byref(pb), C.c_void_p(workspace),
+                                       C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
 def flowmm_flow_exact(params: Params, K: int, Q_full: int, q_strides: Tuple[int, int, int], rho: int, mode: int,

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflowmm.so")
-SOURCES = ["flowmm_api.hip", "profile.hip", "meta.hip", "score.hip", "select.hip", "match.hip", "merge.hip", "unit_path.hip", "flow_exact.hip", "decode.hip"]
+SOURCES = ["flowmm_api.hip", "profile.hip", "meta.hip", "score.hip", "select.hip", "match.hip", "merge.hip", "unit_path.hip", "flow_exact.hip", "decode.hip", "cache.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -534,3 +534,138 @@ FLOWMM_API flowmm_status flowmm_decode_attention(const flowmm_params *p, const v
 }
 
 }  // extern "C"
+
+namespace {
+
+// The single-sequence, single-modality call that a re-merge of one sequence of the cache amounts to.
+struct RemergeCall {
+  flowmm_params one;
+  int32_t cu[2], budget[1], cu_spans[2];
+  flowmm_span span[1];
+  float tau[1];
+  Layout lo;
+  size_t out_bytes, tmp_k, tmp_v, total_bytes;  // merged rows wait behind the ordinary scratch
+};
+
+flowmm_status check_cache_ranges(const flowmm_params *p, const int32_t *cu_capacity) {
+  if (!p) return fail(FLOWMM_EINVAL, "params is NULL");
+  if (!cu_capacity) return fail(FLOWMM_EINVAL, "cu_capacity must not be NULL");
+  if (p->batch < 1) return fail(FLOWMM_EINVAL, "batch must be >= 1");
+  if (cu_capacity[0] != 0) return fail(FLOWMM_EINVAL, "cu_capacity[0] must be 0");
+  for (int b = 0; b < p->batch; ++b)
+    if (cu_capacity[b + 1] <= cu_capacity[b]) return fail(FLOWMM_EINVAL, "cu_capacity must be strictly increasing (sequence %d)", b);
+  return FLOWMM_OK;
+}
+
+flowmm_status build_remerge(const flowmm_params *p, const int32_t *cu_capacity, int32_t seq, int32_t length, RemergeCall &rc) {
+  flowmm_status st = check_cache_ranges(p, cu_capacity);
+  if (st != FLOWMM_OK) return st;
+  if (seq < 0 || seq >= p->batch) return fail(FLOWMM_EINVAL, "sequence %d is outside the batch of %d", seq, p->batch);
+  if (!p->budget_tokens || !p->tau) return fail(FLOWMM_EINVAL, "budget_tokens and tau must not be NULL");
+  const int cap = cu_capacity[seq + 1] - cu_capacity[seq];
+  if (length < 1 || length > cap) return fail(FLOWMM_EINVAL, "length %d of sequence %d is outside [1, capacity=%d]", length, seq, cap);
+  rc.one = *p;
+  rc.cu[0] = 0; rc.cu[1] = length;
+  rc.budget[0] = p->budget_tokens[seq];
+  rc.tau[0] = p->tau[seq];
+  rc.span[0].begin = 0; rc.span[0].end = length; rc.span[0].modality = FLOWMM_TEXT;
+  rc.cu_spans[0] = 0; rc.cu_spans[1] = 1;
+  rc.one.batch = 1;
+  rc.one.cu_seqlens = rc.cu; rc.one.budget_tokens = rc.budget; rc.one.spans = rc.span; rc.one.cu_spans = rc.cu_spans;
+  rc.one.tau = rc.tau;
+  rc.one.theta = -1.0f;  // one modality: rho = 0 and both strategies admit the same pivots
+  if (p->flags & ~(FLOWMM_FLAG_GENERIC_PATH | FLOWMM_FLAG_INVERT_FLOW | FLOWMM_FLAG_WEIGHTED_MERGE))
+    return fail(FLOWMM_EINVAL, "unknown bits in flags");
+  rc.one.flags = p->flags & (FLOWMM_FLAG_GENERIC_PATH | FLOWMM_FLAG_WEIGHTED_MERGE);
+  if ((st = build_layout(&rc.one, rc.lo)) != FLOWMM_OK) return st;
+  const Shape &sh = rc.lo.sh;
+  rc.out_bytes = (size_t)sh.n_layers * sh.Hkv * sh.SB * sh.d * (sh.bf16 ? 2 : 4);
+  rc.tmp_k = align256(rc.lo.workspace_bytes);
+  rc.tmp_v = rc.tmp_k + align256(rc.out_bytes);
+  rc.total_bytes = rc.tmp_v + align256(rc.out_bytes);
+  return FLOWMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+FLOWMM_API flowmm_status flowmm_cache_append(const flowmm_params *p, const int32_t *cu_capacity, const int32_t *lengths,
+                                  void *K_c, void *V_c, const void *k_new, const void *v_new, void *stream) {
+  flowmm_status st = check_cache_ranges(p, cu_capacity);
+  if (st != FLOWMM_OK) return st;
+  if (!lengths) return fail(FLOWMM_EINVAL, "lengths must not be NULL");
+  if (p->n_layers < 1 || p->n_kv_heads < 1) return fail(FLOWMM_EINVAL, "n_layers and n_kv_heads must be >= 1");
+  if (p->dtype != FLOWMM_F32 && p->dtype != FLOWMM_BF16) return fail(FLOWMM_EINVAL, "dtype must be FLOWMM_F32 or FLOWMM_BF16");
+  if (p->head_dim != 64 && p->head_dim != 128) return fail(FLOWMM_EUNSUPPORTED, "head_dim %d is not built (64 and 128 are)", p->head_dim);
+  const int es = p->dtype == FLOWMM_BF16 ? 2 : 4, epc = 16 / es;
+  const int64_t strides[3] = {p->k_stride_layer, p->k_stride_head, p->k_stride_token};
+  for (int i = 0; i < 3; ++i)
+    if (strides[i] < 0 || strides[i] % epc != 0)
+      return fail(FLOWMM_EINVAL, "strides must be non-negative multiples of 16 bytes (%d elements)", epc);
+  if (p->k_stride_token < p->head_dim) return fail(FLOWMM_EINVAL, "token strides must be at least head_dim");
+  if (!K_c || !V_c || !k_new || !v_new) return fail(FLOWMM_EINVAL, "K_c, V_c, k_new and v_new must not be NULL");
+  if (misaligned(K_c) || misaligned(V_c) || misaligned(k_new) || misaligned(v_new))
+    return fail(FLOWMM_EINVAL, "K_c, V_c, k_new and v_new must be 16-byte aligned");
+  for (int b = 0; b < p->batch; ++b) {
+    const int cap = cu_capacity[b + 1] - cu_capacity[b];
+    if (lengths[b] < 0 || lengths[b] > cap) return fail(FLOWMM_EINVAL, "lengths[%d] = %d is outside [0, capacity=%d]", b, lengths[b], cap);
+    if (lengths[b] == cap) return fail(FLOWMM_EINVAL, "the cache of sequence %d is full (%d rows): re-merge it before appending", b, cap);
+  }
+  AppendArgs a;
+  a.K_c = K_c; a.V_c = V_c; a.k_new = k_new; a.v_new = v_new;
+  a.ks_layer = p->k_stride_layer / epc; a.ks_head = p->k_stride_head / epc; a.ks_tok = p->k_stride_token / epc;
+  a.nch = p->head_dim * es / 16; a.batch = p->batch;
+  for (int b0 = 0; b0 < p->batch; b0 += kAppendSeqs) {
+    const int n = p->batch - b0 < kAppendSeqs ? p->batch - b0 : kAppendSeqs;
+    a.b0 = b0;
+    for (int i = 0; i < n; ++i) a.row[i] = cu_capacity[b0 + i] + lengths[b0 + i];
+    const hipError_t e = launch_cache_append(a, n, p->n_kv_heads, p->n_layers, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "cache append kernel");
+  }
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_cache_remerge_sizes(const flowmm_params *p, const int32_t *cu_capacity, int32_t seq,
+                                         int32_t length, size_t plan_bytes[6], size_t *workspace_bytes) {
+  RemergeCall rc;
+  const flowmm_status st = build_remerge(p, cu_capacity, seq, length, rc);
+  if (st != FLOWMM_OK) return st;
+  if (plan_bytes) for (int i = 0; i < 6; ++i) plan_bytes[i] = rc.lo.plan_bytes[i];
+  if (workspace_bytes) *workspace_bytes = rc.total_bytes;
+  return FLOWMM_OK;
+}
+
+FLOWMM_API flowmm_status flowmm_cache_remerge(const flowmm_params *p, const int32_t *cu_capacity, const int32_t *lengths,
+                                   int32_t seq, void *K_c, void *V_c, const void *Q_window,
+                                   const flowmm_plan_buffers *plan, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+  if (!lengths) return fail(FLOWMM_EINVAL, "lengths must not be NULL");
+  if (!p || seq < 0 || seq >= p->batch) return fail(FLOWMM_EINVAL, "params is NULL or the sequence is outside the batch");
+  RemergeCall rc;
+  flowmm_status st = build_remerge(p, cu_capacity, seq, lengths[seq], rc);
+  if (st != FLOWMM_OK) return st;
+  if (!K_c || !V_c) return fail(FLOWMM_EINVAL, "K_c and V_c must not be NULL");
+  if (!workspace) return fail(FLOWMM_EINVAL, "workspace must not be NULL");
+  if (misaligned(workspace)) return fail(FLOWMM_EINVAL, "workspace must be 16-byte aligned");
+  if (workspace_bytes < rc.total_bytes)
+    return fail(FLOWMM_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, rc.total_bytes);
+  const int es = rc.lo.sh.bf16 ? 2 : 4;
+  const size_t seq_off = (size_t)cu_capacity[seq] * (size_t)p->k_stride_token * es;
+  char *Ks = reinterpret_cast<char *>(K_c) + seq_off, *Vs = reinterpret_cast<char *>(V_c) + seq_off;
+  char *ws = reinterpret_cast<char *>(workspace);
+  void *tmp_k = ws + rc.tmp_k, *tmp_v = ws + rc.tmp_v;
+  // the merged rows are written behind the scratch first (the merge reads rows that the result will overwrite)
+  if ((st = check_plan_merge_args(rc.lo, Ks, Vs, Q_window, plan, tmp_k, tmp_v)) != FLOWMM_OK) return st;
+  if ((st = plan_merge_in(rc.lo, Ks, Vs, Q_window, plan, tmp_k, tmp_v, workspace, stream)) != FLOWMM_OK) return st;
+  StoreRowsArgs a;
+  a.K_c = Ks; a.V_c = Vs; a.K_src = tmp_k; a.V_src = tmp_v;
+  const int epc = 16 / es;
+  a.ks_layer = p->k_stride_layer / epc; a.ks_head = p->k_stride_head / epc; a.ks_tok = p->k_stride_token / epc;
+  a.nch = rc.lo.sh.d * es / 16; a.B = rc.lo.sh.SB; a.row0 = 0;
+  const hipError_t e = launch_cache_store_rows(a, rc.lo.sh.Hkv, rc.lo.sh.n_layers, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "cache store kernel");
+  return FLOWMM_OK;
+}
+
+}  // extern "C"

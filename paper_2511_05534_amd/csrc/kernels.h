@@ -91,6 +91,26 @@ struct DecodeArgs {
 int decode_splits(const Shape &sh);
 hipError_t launch_decode_attention(const Ctx &c, const DecodeArgs &a);
 
+// cache append (decode-time maintenance): one new K and V row per sequence, (layer, kv head) by (layer, kv head)
+constexpr int kAppendSeqs = 64;  // sequences per launch (their target rows ride in the kernel arguments)
+struct AppendArgs {
+  void *K_c, *V_c;               // the cache, addressed through the strides below (16-byte chunks)
+  const void *k_new, *v_new;     // [Lyr][Hkv][batch][d] contiguous
+  long long ks_layer, ks_head, ks_tok;
+  int nch, batch, b0;            // chunks per row; batch of the call; first sequence of this launch
+  int row[kAppendSeqs];          // cache row (token index) that sequence b0 + i appends to
+};
+hipError_t launch_cache_append(const AppendArgs &a, int n_seqs, int Hkv, int n_layers, hipStream_t stream);
+
+// rows of a dense [Lyr][Hkv][B][d] pair of tensors stored to cache rows [row0, row0 + B)
+struct StoreRowsArgs {
+  void *K_c, *V_c;
+  const void *K_src, *V_src;
+  long long ks_layer, ks_head, ks_tok;
+  int nch, B, row0;
+};
+hipError_t launch_cache_store_rows(const StoreRowsArgs &a, int Hkv, int n_layers, hipStream_t stream);
+
 constexpr int kMetaChunkWords = 960;
 struct MetaChunk { int w[kMetaChunkWords]; };
 

@@ -13,7 +13,9 @@ namespace {
 
 const char *const kNames[KID_COUNT] = {"meta_upload", "expand_modality", "score_stats", "score_combine",
                                        "score_colsum", "select", "match", "merge_csr", "merge_tasks",
-                                       "merge_fold",                                        "unit_plan", "unit_match", "unit_merge", "unit_flow_merge", "flow_exact", "decode_partial", "decode_combine"};
+                                       "merge_fold", "unit_plan", "unit_match", "unit_merge", "unit_flow_merge",
+                                       "flow_exact", "decode_partial", "decode_combine", "cache_append",
+                                       "cache_store_rows"};
 
 struct Record { int id; hipEvent_t start, stop; };
 

@@ -162,3 +162,34 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
                 fb.flowmm_plan_merge_static(p, far[0], far[1], far[2], plan, far[3], far[4])
             assert ei.value.status == fb.FLOWMM_EWORKSPACE
             assert str(ws) in ei.value.message and str(cap) in ei.value.message
+
+
+def test_cache_maintenance_argument_checks():
+    """flowmm_cache_append / flowmm_cache_remerge validate on the host before any HIP call."""
+    p = params_for(seqlens=[40, 50], budgets=[30, 40], spans=[[(0, 40, 0)], [(0, 50, 0)]], window=8)
+    good, far = 0x10000, [1 << 40, 1 << 41, 1 << 42]
+    cap = [0, 40, 90]
+    bad = [
+        (lambda: fb.flowmm_cache_append(p, cap, [30, 50], good, far[0], far[1], far[2]), "full"),
+        (lambda: fb.flowmm_cache_append(p, cap, [30, 51], good, far[0], far[1], far[2]), "outside"),
+        (lambda: fb.flowmm_cache_append(p, [0, 40, 40], [30, 40], good, far[0], far[1], far[2]), "increasing"),
+        (lambda: fb.flowmm_cache_append(p, [1, 40, 90], [30, 40], good, far[0], far[1], far[2]), "cu_capacity[0]"),
+        (lambda: fb.flowmm_cache_append(p, cap, [30, 40], 0, far[0], far[1], far[2]), "NULL"),
+        (lambda: fb.flowmm_cache_append(p, cap, [30, 40], good + 4, far[0], far[1], far[2]), "aligned"),
+        (lambda: fb.flowmm_cache_remerge_sizes(p, cap, 2, 40), "outside the batch"),
+        (lambda: fb.flowmm_cache_remerge_sizes(p, cap, 1, 51), "capacity"),
+        (lambda: fb.flowmm_cache_remerge_sizes(p, cap, 1, 39), "budget"),   # fewer rows than the budget
+        (lambda: fb.flowmm_cache_remerge(p, cap, [40, 50], 0, good, far[0], 0, [good] * 6, far[1], 1 << 30), "NULL"),
+        (lambda: fb.flowmm_cache_remerge(p, cap, [40, 50], 0, good, far[0], far[2], [good] * 6, 0, 1 << 30), "NULL"),
+    ]
+    for call, word in bad:
+        with pytest.raises(fb.FlowMMError) as ei:
+            call()
+        assert ei.value.status == fb.FLOWMM_EINVAL and word in ei.value.message, ei.value.message
+    sizes, ws = fb.flowmm_cache_remerge_sizes(p, cap, 1, 50)
+    assert sizes == [2 * 2 * 50 * 4, 2 * 4, 2 * 4, 2 * 2 * 40 * 4, 2 * 2 * 50 * 4, 2 * 2 * 4]
+    out_bytes = 2 * 2 * 40 * 128 * 2
+    assert ws % 256 == 0 and ws >= 2 * out_bytes
+    with pytest.raises(fb.FlowMMError) as ei:
+        fb.flowmm_cache_remerge(p, cap, [40, 50], 1, good, far[0], far[2], [good] * 6, far[1], ws - 1)
+    assert ei.value.status == fb.FLOWMM_EWORKSPACE

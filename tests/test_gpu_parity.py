@@ -552,3 +552,117 @@ def test_planted_zero_rows_multiples_and_ties(oracle, path, theta):
             # a zero-norm evicted key has cosine 0 with every pivot: any eligible slot is a tie; it must not be dropped
             assert asg[10] >= 0
     print(rep, flush=True)
+
+
+CACHE_CASES = {
+    # prefill shape, head room R per sequence, sequence to re-merge, flags of the re-merge
+    "short_unit_path": dict(shape=dict(Hq=4, Hkv=2, W=16, spans=((40, 300, 60),), pct=(15,)), R=24, seq=0, flags=0),
+    "short_generic_kernels": dict(shape=dict(Hq=4, Hkv=2, W=16, spans=((40, 300, 60),), pct=(15,)), R=24, seq=0, flags=1),
+    "many_rows_gqa": dict(shape=dict(Hq=6, Hkv=2, W=32, spans=((100, 2300, 50, 1700, 77),), pct=(30,), n_layers=1), R=200, seq=0, flags=0),
+    "f32_d64": dict(shape=dict(dtype="f32", Hq=4, Hkv=4, d=64, W=8, spans=((32, 256, 32),), pct=(20,)), R=19, seq=0, flags=0),
+    "batch_of_3_middle_sequence": dict(shape=dict(Hq=4, Hkv=2, W=16, spans=((30, 260, 40), (64, 700, 69), (20, 100, 17)),
+                                                  pct=(10, 20, 15)), R=33, seq=1, flags=0),
+    "weighted_merge": dict(shape=dict(Hq=2, Hkv=2, W=8, spans=((30, 400, 50),), pct=(10,)), R=40, seq=0, flags=4),
+}
+
+
+@pytest.mark.parametrize("name", list(CACHE_CASES))
+def test_cache_append_and_remerge(oracle, name):
+    """Decode-time maintenance through the C ABI: flowmm_cache_append (cache-append equation of the
+    Preliminary section) fills the head room behind the merged prompt rows token by token, bit-exact
+    against the oracle's append; flowmm_cache_remerge compresses one sequence back to its budget and is
+    compared stage by stage with the oracle run on the same cache rows as a single-modality prompt."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    case = CACHE_CASES[name]
+    w = small(name, **case["shape"])
+    R, seq, flags = case["R"], case["seq"], case["flags"]
+    dev, tdt = "cuda:0", (torch.bfloat16 if w.dtype == "bf16" else torch.float32)
+    Lyr, Hq, Hkv, d, W, batch = w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.window, w.batch
+    K, V, Q = upload(w)
+    pre = fb.DeviceBuffers(fb.Params.from_workload(w))
+    pre.plan_merge(K, V, Q)
+    # the cache: per sequence its merged prompt rows and R rows of head room
+    Bs = list(w.budgets)
+    cu_cap = np.concatenate([[0], np.cumsum([B + R for B in Bs])]).astype(np.int32)
+    cuk = w.cu_kept
+    Kc = torch.full((Lyr, Hkv, int(cu_cap[-1]), d), 3.0, dtype=tdt, device=dev)
+    Vc = torch.full_like(Kc, -3.0)
+    for b in range(batch):
+        Kc[:, :, cu_cap[b]:cu_cap[b] + Bs[b]] = pre.K_out[:, :, cuk[b]:cuk[b + 1]]
+        Vc[:, :, cu_cap[b]:cu_cap[b] + Bs[b]] = pre.V_out[:, :, cuk[b]:cuk[b + 1]]
+    tau = [4.0 / B for B in Bs]
+    cache = fb.Params(Lyr, Hq, Hkv, d, w.dtype, [B + R for B in Bs], Bs, [[(0, B + R, 0)] for B in Bs], W, 0.0, tau,
+                      q_strides=(Hq * W * d, W * d, d), flags=flags)
+    # host mirror of the cache, maintained by the oracle
+    mirror_k, mirror_v = Kc.float().cpu().numpy(), Vc.float().cpu().numpy()
+    lengths = list(Bs)
+    gen = torch.Generator(device=dev).manual_seed(123)
+    for step in range(R):
+        k_new = torch.randn((Lyr, Hkv, batch, d), generator=gen, device=dev).to(tdt)
+        v_new = torch.randn((Lyr, Hkv, batch, d), generator=gen, device=dev).to(tdt)
+        fb.flowmm_cache_append(cache, cu_cap, lengths, Kc.data_ptr(), Vc.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                               torch.cuda.current_stream().cuda_stream)
+        kh, vh = k_new.float().cpu().numpy(), v_new.float().cpu().numpy()
+        for b in range(batch):
+            for l in range(Lyr):
+                mk = np.ascontiguousarray(mirror_k[l][:, cu_cap[b]:cu_cap[b + 1]])
+                mv = np.ascontiguousarray(mirror_v[l][:, cu_cap[b]:cu_cap[b + 1]])
+                assert oracle.cache_append(mk, mv, lengths[b], kh[l][:, b], vh[l][:, b]) == lengths[b] + 1
+                mirror_k[l][:, cu_cap[b]:cu_cap[b + 1]] = mk
+                mirror_v[l][:, cu_cap[b]:cu_cap[b + 1]] = mv
+            lengths[b] += 1
+    torch.cuda.synchronize()
+    assert (Kc.float().cpu().numpy() == mirror_k).all() and (Vc.float().cpu().numpy() == mirror_v).all()
+    # every sequence is full now: one more append is refused on the host
+    with pytest.raises(fb.FlowMMError) as ei:
+        fb.flowmm_cache_append(cache, cu_cap, lengths, Kc.data_ptr(), Vc.data_ptr(), k_new.data_ptr(), v_new.data_ptr())
+    assert ei.value.status == fb.FLOWMM_EINVAL and "full" in ei.value.message
+
+    # re-merge one sequence
+    n, B = lengths[seq], Bs[seq]
+    Qw = torch.randn((Lyr, Hq, W, d), generator=gen, device=dev).to(tdt)
+    sizes, ws_bytes = fb.flowmm_cache_remerge_sizes(cache, cu_cap, seq, n)
+    assert sizes[0] == Lyr * Hkv * n * 4 and sizes[3] == Lyr * Hkv * B * 4
+    plan = {"importance": torch.empty((Lyr, Hkv, n), dtype=torch.float32, device=dev),
+            "rho": torch.empty((Lyr, 1), dtype=torch.float32, device=dev),
+            "mode": torch.empty((Lyr, 1), dtype=torch.int32, device=dev),
+            "kept_idx": torch.empty((Lyr, Hkv, B), dtype=torch.int32, device=dev),
+            "assign": torch.empty((Lyr, Hkv, n), dtype=torch.int32, device=dev),
+            "n_dropped": torch.empty((Lyr, Hkv, 1), dtype=torch.int32, device=dev)}
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    fb.flowmm_cache_remerge(cache, cu_cap, lengths, seq, Kc.data_ptr(), Vc.data_ptr(), Qw.data_ptr(),
+                            [plan[f].data_ptr() for f in fb.PLAN_FIELDS], workspace.data_ptr(), ws_bytes,
+                            torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    after_k, after_v = Kc.float().cpu().numpy(), Vc.float().cpu().numpy()
+    lo, hi = int(cu_cap[seq]), int(cu_cap[seq + 1])
+    # nothing outside rows [0, B) of the sequence's range has changed
+    keep = np.ones(after_k.shape[2], dtype=bool)
+    keep[lo:lo + B] = False
+    assert (after_k[:, :, keep] == mirror_k[:, :, keep]).all() and (after_v[:, :, keep] == mirror_v[:, :, keep]).all()
+    # the plan and the merged rows against the oracle on the same cache rows (one modality, the last W rows are the proxies)
+    as_prompt = wl.make_workload("cache_rows", w.dtype, 0, Lyr, Hq, Hkv, d, W, [[n]], [100], theta=-1.0, budgets=[B])
+    as_prompt.tau = [tau[seq]]
+    gpu = {f: plan[f].cpu().numpy() for f in fb.PLAN_FIELDS}
+    gpu["K_out"], gpu["V_out"] = after_k[:, :, lo:lo + B], after_v[:, :, lo:lo + B]
+    qh = Qw.float().cpu().numpy()
+    rep = Report()
+    for l in range(Lyr):
+        rows_k = np.ascontiguousarray(mirror_k[l][:, lo:lo + n])
+        rows_v = np.ascontiguousarray(mirror_v[l][:, lo:lo + n])
+        check_layer(oracle, as_prompt, gpu, l, report=rep, tensors_np=(rows_k, rows_v, qh[l]), flags=flags & 4)
+        assert gpu["rho"][l][0] == 0.0
+        if not flags & 4:
+            # the oracle's own re-merge from the GPU's decisions is covered by check_layer; its bookkeeping here
+            mk, mv = rows_k.copy(), rows_v.copy()
+            _, new_len = oracle.cache_remerge(mk, mv, n, qh[l], B, w.dtype, tau[seq])
+            assert new_len == B
+    print(rep, flush=True)
+    # the books: the sequence is back at its budget and takes tokens again
+    lengths[seq] = B
+    others_full = [b for b in range(batch) if b != seq]
+    if not others_full:
+        fb.flowmm_cache_append(cache, cu_cap, lengths, Kc.data_ptr(), Vc.data_ptr(), k_new.data_ptr(), v_new.data_ptr())
+        torch.cuda.synchronize()
+        assert torch.equal(Kc[:, :, lo + B], k_new[:, :, seq]) and torch.equal(Vc[:, :, lo + B], v_new[:, :, seq])
