@@ -138,6 +138,53 @@ __device__ __forceinline__ void load_to_lds(const void *base, unsigned byte_off,
 #pragma clang diagnostic pop
 }
 
+// The rows of 32 tokens as MFMA operand fragments (this lane's chunks 2t+half of row n), fetched as
+// whole rows.  Asked for straight from memory, those fragments make every load instruction touch 32
+// cache lines for 32 bytes each, and a compute unit's L1 looks up one line per clock: 16 bytes per
+// clock, and the waves wait at their load instructions meanwhile.  Here the wave fetches whole rows
+// (64/NCH rows per instruction, every line touched once) into a staging area of its own in LDS with
+// direct global->LDS loads; the chunk a lane asks for is chosen so that the chunks of row r land
+// XOR-swizzled by r, and the fragments are then read from there without bank conflicts.
+//   base  : wave-uniform; row t starts at base + t * row_stride chunks (32-bit byte offsets: the
+//           caller has checked that the rows lie within 4 GiB of base)
+//   tok   : the row this lane's fragments belong to (lanes n and n + 32 pass the same)
+//   stage : 32 * NCH chunks of LDS that no other wave touches until the call has returned
+template <bool BF16, int D>
+__device__ __forceinline__ void request_rows_staged(const void *base, unsigned row_stride, int tok, uint4 *stage) {
+  constexpr int NCH = Cfg<BF16, D>::NCH;
+  static_assert(NCH <= 64 && (NCH & (NCH - 1)) == 0, "rows of a power-of-two number of chunks");
+  constexpr int RPI = 64 / NCH;  // rows per load instruction
+  const int lane = threadIdx.x & 63;
+  const int rl = lane / NCH, slot = lane % NCH;
+#pragma unroll
+  for (int j = 0; j < 32 / RPI; ++j) {
+    const int r = j * RPI + rl;
+    const int t = __shfl(tok, r, 64);
+    const int ch = slot ^ (r & (NCH - 1));
+    load_to_lds<16>(base, ((unsigned)t * row_stride + (unsigned)ch) * 16u, stage + j * 64);
+  }
+}
+
+// The fragments of the rows that request_rows_staged asked for (waits for this wave's outstanding loads
+// first; only this wave reads the area, so no barrier), and a wait for the reads themselves: on return
+// the area may be written again.
+template <bool BF16, int D>
+__device__ __forceinline__ void read_rows_staged(const uint4 *stage, uint4 (&frag)[Cfg<BF16, D>::NF]) {
+  constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF;
+  const int lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
+  __builtin_amdgcn_s_waitcnt(0);
+#pragma unroll
+  for (int f = 0; f < NF; ++f) frag[f] = stage[n * NCH + ((2 * f + half) ^ (n & (NCH - 1)))];
+  __builtin_amdgcn_s_waitcnt(0);
+}
+
+template <bool BF16, int D>
+__device__ __forceinline__ void fetch_rows_staged(const void *base, unsigned row_stride, int tok, uint4 *stage,
+                                                  uint4 (&frag)[Cfg<BF16, D>::NF]) {
+  request_rows_staged<BF16, D>(base, row_stride, tok, stage);
+  read_rows_staged<BF16, D>(stage, frag);
+}
+
 // For grids whose x extent counts sequences (or a fixed number of workgroups per sequence) and whose
 // y, z are kv head and layer: workgroups go to the eight XCDs in turn by their linear index, so a
 // batch of eight would pin each sequence, long ones included, to one XCD.  Rotating x by the other

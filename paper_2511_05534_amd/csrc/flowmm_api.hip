@@ -89,11 +89,25 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
 
   const int batch = p->batch;
   const int match_tile = match_tile_tokens(sh.bf16), score_tile = score_tile_keys(sh.bf16);
+  // key tiles a score workgroup walks over (it stages the query rows once per run): as many as leave
+  // every compute unit a few workgroups
+  int tpw = 1;
+  {
+    long long tiles = 0;
+    for (int b = 0; b < batch; ++b) {
+      const long long L = (long long)p->cu_seqlens[b + 1] - p->cu_seqlens[b];
+      if (L > 0) tiles += (L + score_tile - 1) / score_tile;
+    }
+    tiles *= (long long)p->n_layers * p->n_kv_heads;
+    while (tpw < 8 && tiles / (2 * tpw) >= 4 * 256) tpw *= 2;
+  }
+  sh.score_tpw = tpw;
   std::vector<int32_t> cu_score(batch + 1, 0), cu_match(batch + 1, 0), cu_task(batch + 1, 0),
       cu_multi(batch + 1, 0), cu_part(batch + 1, 0), cu_bp(batch + 1, 0), cu_flowq(batch + 1, 0);
   std::vector<int32_t> seq((size_t)batch * SW_WORDS, 0);
   int64_t sumB = 0;
   int maxB = 0, maxL = 0, maxE = 0;
+  sh.rows32 = 1;
   for (int b = 0; b < batch; ++b) {
     const int64_t L64 = (int64_t)p->cu_seqlens[b + 1] - p->cu_seqlens[b];
     if (L64 < 1) return fail(FLOWMM_EINVAL, "cu_seqlens must be strictly increasing (sequence %d)", b);
@@ -117,7 +131,8 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     }
     if (pos != L) return fail(FLOWMM_EINVAL, "spans of sequence %d cover [0,%d), not [0,%d)", b, pos, L);
     const int E = L - B;
-    cu_score[b + 1] = cu_score[b] + (L + score_tile - 1) / score_tile;
+    if (((int64_t)(L - 1) * p->k_stride_token + p->head_dim) * es >= (int64_t)1 << 32) sh.rows32 = 0;
+    cu_score[b + 1] = cu_score[b] + ((L + score_tile - 1) / score_tile + tpw - 1) / tpw;
     // an intra-modal layer matches text and image tokens in separate tiles: one tile more at most
     cu_match[b + 1] = cu_match[b] + (L + match_tile - 1) / match_tile + 1;
     cu_bp[b + 1] = cu_bp[b] + (B + 31) / 32 * 32;

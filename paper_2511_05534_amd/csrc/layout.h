@@ -14,7 +14,7 @@ enum MetaWord {
   MW_OFF_SEQ,      // word offset of the per-sequence records
   MW_OFF_SPANS,    // word offset of the spans (begin, end, modality), all sequences
   MW_N_SPANS,
-  MW_OFF_CU_SCORE, // word offset of cu_tiles_score[batch+1]
+  MW_OFF_CU_SCORE, // word offset of cu_runs_score[batch+1]: runs of key tiles of the score kernels
   MW_OFF_CU_MATCH, // word offset of cu_tiles_match[batch+1]
   MW_OFF_CU_TASK,  // word offset of cu_tasks[batch+1]   (upper bounds)
   MW_OFF_CU_MULTI, // word offset of cu_multi[batch+1]   (upper bounds)
@@ -63,10 +63,13 @@ struct Shape {
   int n_layers, Hq, Hkv, G, d, bf16;
   int batch, T, SB, W, W_pad, R_pad, maxB, maxL, maxE, n_spans;
   int unit_path;  // 1: every unit is handled by one workgroup (unit_path.hip)
+  int rows32;     // 1: the K rows of every sequence lie within 4 GiB of the sequence's first row (32-bit byte offsets)
   int invert_flow;     // 1: the misaligned strategy (cross-modal merging iff NOT rho > theta)
   int weighted_merge;  // 1: similarity-weighted mean instead of the uniform one
   int SBP;        // sum over sequences of the budget rounded up to a multiple of 32
-  int tiles_score, tiles_match, tasks_total, multi_total, part_total, flowq_total;
+  int tiles_score;  // runs of key tiles over all sequences: one score workgroup and one set of partials per run
+  int score_tpw;    // key tiles per run (the last run of a sequence may be shorter)
+  int tiles_match, tasks_total, multi_total, part_total, flowq_total;
   float scale_log2e, theta;
   long long ks_layer, ks_head, ks_tok;  // K/V strides in 16-byte chunks
   long long qs_layer, qs_head, qs_tok;  // Q strides in 16-byte chunks

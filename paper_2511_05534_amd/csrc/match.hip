@@ -110,8 +110,6 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
     if (wave * 64 + lane < rows)
       load_to_lds<4>(pl_w + r0, (unsigned)(wave * 64 + lane) * 4u, lds_w + buf * ROWS + wave * 64);
   };
-  if (ntiles > 0) stage(0, 0);
-
   // this wave's tokens as B operands, and their norms
   const int wv0 = v0 + wave * 32 * KS;
   const bool active = wv0 < cn;
@@ -129,12 +127,24 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
     tok[sub] = token_of(sub);
     state[sub] = assign[tok[sub]];
   }
+  // Their rows come in whole through the LDS that the pivot tiles use afterwards (every wave has its own
+  // share of it), one token group at a time; rows that do not lie within 4 GiB, and rows too wide for that
+  // share, are fetched fragment by fragment.
+  constexpr bool kStaged = 8 * 32 * NCH <= 2 * ROWS * RS;
+  if (kStaged && sh.rows32) {
 #pragma unroll
-  for (int sub = 0; sub < KS; ++sub) {
-    const uint4 *row = K + (long long)tok[sub] * sh.ks_tok + half;
+    for (int sub = 0; sub < KS; ++sub)
+      fetch_rows_staged<BF16, D>(K, (unsigned)sh.ks_tok, tok[sub], lds_rows + wave * 32 * NCH, kf[sub]);
+    __syncthreads();  // the pivot tiles may overwrite the other waves' shares now
+  } else {
 #pragma unroll
-    for (int f = 0; f < NF; ++f) kf[sub][f] = row[2 * f];
+    for (int sub = 0; sub < KS; ++sub) {
+      const uint4 *row = K + (long long)tok[sub] * sh.ks_tok + half;
+#pragma unroll
+      for (int f = 0; f < NF; ++f) kf[sub][f] = row[2 * f];
+    }
   }
+  if (ntiles > 0) stage(0, 0);
 #pragma unroll
   for (int sub = 0; sub < KS; ++sub)
     if (half == 0)

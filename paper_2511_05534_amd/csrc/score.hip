@@ -24,12 +24,13 @@ namespace {
 constexpr int kThreads = kScoreWaves * 64;
 
 struct TileCtx {
-  int b, tile, x, gkv, l, wave, lane, n, half, key0;  // key0: first key of this wave
-  bool masked;                                        // some key of the tile is hidden from some window row
+  int b, tile, x, gkv, l, wave, lane, n, half, key0;  // key0: first key of this wave in the current tile
+  int tile_end;                                       // the run covers tiles [tile, tile_end) of sequence b
+  bool masked;                                        // some key of the current tile is hidden from some window row
   SeqInfo s;
 };
 
-// Workgroups are handed to the eight XCDs in turn; all key tiles of a (layer, kv head) go to one
+// Workgroups are handed to the eight XCDs in turn; all runs of a (layer, kv head) go to one
 // XCD so that its query rows sit in one L2.  Returns false for the padding workgroups.
 template <int TILE>
 __device__ __forceinline__ bool tile_ctx(const Ctx &c, TileCtx &t) {
@@ -44,8 +45,9 @@ __device__ __forceinline__ bool tile_ctx(const Ctx &c, TileCtx &t) {
   t.gkv = unit - t.l * sh.Hkv;
   const int *cu = meta + meta[MW_OFF_CU_SCORE];
   t.b = find_seq(cu, meta[MW_BATCH], t.x);
-  t.tile = t.x - cu[t.b];
   t.s = load_seq(meta, t.b);
+  t.tile = (t.x - cu[t.b]) * sh.score_tpw;
+  t.tile_end = min(t.tile + sh.score_tpw, (t.s.L + TILE - 1) / TILE);
   t.wave = threadIdx.x >> 6;
   t.lane = threadIdx.x & 63;
   t.n = t.lane & 31;
@@ -53,6 +55,14 @@ __device__ __forceinline__ bool tile_ctx(const Ctx &c, TileCtx &t) {
   t.key0 = t.tile * TILE + t.wave * (TILE / kScoreWaves);
   t.masked = (t.tile + 1) * TILE > t.s.L - sh.W;
   return true;
+}
+
+// position the context on tile `tile` of the run
+template <int TILE>
+__device__ __forceinline__ void set_tile(const Ctx &c, TileCtx &t, int tile) {
+  t.tile = tile;
+  t.key0 = tile * TILE + t.wave * (TILE / kScoreWaves);
+  t.masked = (tile + 1) * TILE > t.s.L - c.sh.W;
 }
 
 // Request the R_pad query rows of this (sequence, layer, kv head) into LDS, row stride NCH+1
@@ -152,12 +162,20 @@ __device__ __forceinline__ void stats_body(const Ctx &c, const TileCtx &t, const
     }
     const float m2 = __shfl_xor(m, 32, 64), z2 = __shfl_xor(z, 32, 64);
     stat_combine(m, z, m2, z2);
-    // log2 of the row's sum of 2^logit over this wave's keys: the pair (that, 1) stands for (m, z)
-    if (t.half == 0) lds_stats[t.wave * sh.R_pad + row] = m + __builtin_amdgcn_logf(z);
+    // log2 of the row's sum of 2^logit over this wave's keys so far in the run: the pair (that, 1)
+    // stands for (m, z); the slot belongs to this lane, earlier tiles of the run left their sum there
+    if (t.half == 0) {
+      float *slot = lds_stats + t.wave * sh.R_pad + row;
+      float m0 = *slot, z0 = m0 == -INFINITY ? 0.f : 1.f;
+      stat_combine(m0, z0, m, z);
+      *slot = z0 > 0.f ? m0 + __builtin_amdgcn_logf(z0) : -INFINITY;
+    }
   }
 }
 
-template <bool BF16, int D>
+// RUN: the workgroup may have several tiles (a loop around the tile costs a few registers that the
+// one-tile kernel, which small workloads get, does not have to spill)
+template <bool BF16, int D, bool RUN>
 __global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF, KS = score_subs(BF16);
   extern __shared__ uint4 lds[];
@@ -169,13 +187,21 @@ __global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
   uint4 kf[KS][NF];
   load_keys<BF16, D, KS>(c, t, kf);  // the long way first (HBM); the query rows come from L2
   stage_queries<BF16, D>(c, t, ldsq);
+  for (int row = t.lane; row < sh.R_pad; row += 64) lds_stats[t.wave * sh.R_pad + row] = -INFINITY;
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
-  if (t.key0 < t.s.L) {  // waves past the end of the sequence have nothing to add
-    if (t.masked) stats_body<BF16, D, KS, true>(c, t, kf, ldsq, lds_stats);
-    else stats_body<BF16, D, KS, false>(c, t, kf, ldsq, lds_stats);
-  } else {
-    for (int row = t.lane; row < sh.R_pad; row += 64) lds_stats[t.wave * sh.R_pad + row] = -INFINITY;
+  // the run's tiles one after the other on the same query rows; the workgroup that shares the compute
+  // unit computes while this one waits for its next keys
+  const int tile_end = RUN ? t.tile_end : t.tile + 1;
+  for (int tile = t.tile; tile < tile_end; ++tile) {
+    if (tile != t.tile) {
+      set_tile<score_tile_keys(BF16)>(c, t, tile);
+      load_keys<BF16, D, KS>(c, t, kf);
+    }
+    if (t.key0 < t.s.L) {  // waves past the end of the sequence have nothing to add
+      if (t.masked) stats_body<BF16, D, KS, true>(c, t, kf, ldsq, lds_stats);
+      else stats_body<BF16, D, KS, false>(c, t, kf, ldsq, lds_stats);
+    }
   }
   __syncthreads();
   float2 *out = c.part_stats + ((long long)(t.l * sh.Hkv + t.gkv) * sh.tiles_score + t.x) * sh.R_pad;
@@ -183,7 +209,10 @@ __global__ __launch_bounds__(kThreads, 4) void score_stats_kernel(Ctx c) {
     float2 a = make_float2(lds_stats[row], 1.f);
     if (a.x == -INFINITY) a.y = 0.f;
 #pragma unroll
-    for (int w = 1; w < kScoreWaves; ++w) stat_combine(a.x, a.y, lds_stats[w * sh.R_pad + row], 1.f);
+    for (int w = 1; w < kScoreWaves; ++w) {
+      const float o = lds_stats[w * sh.R_pad + row];
+      stat_combine(a.x, a.y, o, o == -INFINITY ? 0.f : 1.f);
+    }
     out[row] = a;
   }
 }
@@ -269,13 +298,13 @@ __device__ __forceinline__ void colsum_body(const Ctx &c, const TileCtx &t, cons
     if (++rbh == bph) {
       rbh = 0;
       const float v = wave_sum(cross_acc);
-      if (t.lane == 0) lds_cross[t.wave * sh.G + rb / bph] = v;
+      if (t.lane == 0) lds_cross[t.wave * sh.G + rb / bph] += v;  // over the tiles of the run
       cross_acc = 0.f;
     }
   }
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool RUN>
 __global__ __launch_bounds__(kThreads, 4) void score_colsum_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH, NF = Cfg<BF16, D>::NF, KS = score_subs(BF16);
   extern __shared__ uint4 lds[];
@@ -305,10 +334,22 @@ __global__ __launch_bounds__(kThreads, 4) void score_colsum_kernel(Ctx c) {
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
-  float colsum[KS];
+  // the run's tiles one after the other on the same query rows (see score_stats_kernel)
+  const int tile_end = RUN ? t.tile_end : t.tile + 1;
+  for (int tile = t.tile; tile < tile_end; ++tile) {
+    if (tile != t.tile) {
+      set_tile<score_tile_keys(BF16)>(c, t, tile);
+      load_keys<BF16, D, KS>(c, t, kf);
 #pragma unroll
-  for (int sub = 0; sub < KS; ++sub) colsum[sub] = 0.f;
-  if (t.key0 < t.s.L) {
+      for (int sub = 0; sub < KS; ++sub) {
+        const int key = t.key0 + sub * 32 + t.n;
+        keymod[sub] = mod[key < t.s.L ? key : t.s.L - 1];
+      }
+    }
+    if (t.key0 >= t.s.L) continue;  // this wave's keys lie past the end of the sequence
+    float colsum[KS];
+#pragma unroll
+    for (int sub = 0; sub < KS; ++sub) colsum[sub] = 0.f;
     const bool win_img = t.s.win_has_img != 0;
     if (t.masked) {
       if (win_img) colsum_body<BF16, D, KS, true, true>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
@@ -317,14 +358,14 @@ __global__ __launch_bounds__(kThreads, 4) void score_colsum_kernel(Ctx c) {
       if (win_img) colsum_body<BF16, D, KS, false, true>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
       else colsum_body<BF16, D, KS, false, false>(c, t, kf, keymod, ldsq, lds_c, lds_rowimg, lds_cross, colsum);
     }
-  }
-  const float inv_rows = 1.0f / (float)(sh.G * sh.W);
-  float *imp = c.importance + (long long)(t.l * sh.Hkv + t.gkv) * sh.T + t.s.tok_off;
+    const float inv_rows = 1.0f / (float)(sh.G * sh.W);
+    float *imp = c.importance + (long long)(t.l * sh.Hkv + t.gkv) * sh.T + t.s.tok_off;
 #pragma unroll
-  for (int sub = 0; sub < KS; ++sub) {
-    const int key = t.key0 + sub * 32 + t.n;
-    const float tot = colsum[sub] + __shfl_xor(colsum[sub], 32, 64);
-    if (t.half == 0 && key < t.s.L) imp[key] = tot * inv_rows;
+    for (int sub = 0; sub < KS; ++sub) {
+      const int key = t.key0 + sub * 32 + t.n;
+      const float tot = colsum[sub] + __shfl_xor(colsum[sub], 32, 64);
+      if (t.half == 0 && key < t.s.L) imp[key] = tot * inv_rows;
+    }
   }
   __syncthreads();
   for (int g = threadIdx.x; g < sh.G; g += kThreads) {
@@ -335,7 +376,7 @@ __global__ __launch_bounds__(kThreads, 4) void score_colsum_kernel(Ctx c) {
   }
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool RUN>
 hipError_t launch_score_t(const Ctx &c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   const Shape &sh = c.sh;
@@ -343,16 +384,16 @@ hipError_t launch_score_t(const Ctx &c) {
   const size_t lds1 = q_bytes + (size_t)kScoreWaves * sh.R_pad * sizeof(float);
   const size_t lds3 = q_bytes + (size_t)sh.R_pad * 4 + (size_t)sh.W_pad * 4 + (size_t)kScoreWaves * sh.G * 4;
   hipError_t e;
-  e = allow_full_lds<score_stats_kernel<BF16, D>>();
+  e = allow_full_lds<score_stats_kernel<BF16, D, RUN>>();
   if (e != hipSuccess) return e;
-  e = allow_full_lds<score_colsum_kernel<BF16, D>>();
+  e = allow_full_lds<score_colsum_kernel<BF16, D, RUN>>();
   if (e != hipSuccess) return e;
   const int units = sh.n_layers * sh.Hkv;
   const long long grid = (long long)((units + 7) / 8) * 8 * sh.tiles_score;
   if (grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
   {
     ProfScope ps(c.stream, KID_SCORE_STATS);
-    score_stats_kernel<BF16, D><<<dim3((unsigned)grid), kThreads, lds1, c.stream>>>(c);
+    score_stats_kernel<BF16, D, RUN><<<dim3((unsigned)grid), kThreads, lds1, c.stream>>>(c);
   }
   {
     ProfScope ps(c.stream, KID_SCORE_COMBINE);
@@ -360,9 +401,14 @@ hipError_t launch_score_t(const Ctx &c) {
   }
   {
     ProfScope ps(c.stream, KID_SCORE_COLSUM);
-    score_colsum_kernel<BF16, D><<<dim3((unsigned)grid), kThreads, lds3, c.stream>>>(c);
+    score_colsum_kernel<BF16, D, RUN><<<dim3((unsigned)grid), kThreads, lds3, c.stream>>>(c);
   }
   return hipGetLastError();
+}
+
+template <bool BF16, int D>
+hipError_t launch_score_r(const Ctx &c) {
+  return c.sh.score_tpw > 1 ? launch_score_t<BF16, D, true>(c) : launch_score_t<BF16, D, false>(c);
 }
 
 }  // namespace
@@ -374,8 +420,8 @@ size_t score_lds_bytes(const Shape &sh) {
 }
 
 hipError_t launch_score(const Ctx &c) {
-  if (c.sh.bf16) return c.sh.d == 128 ? launch_score_t<true, 128>(c) : launch_score_t<true, 64>(c);
-  return c.sh.d == 128 ? launch_score_t<false, 128>(c) : launch_score_t<false, 64>(c);
+  if (c.sh.bf16) return c.sh.d == 128 ? launch_score_r<true, 128>(c) : launch_score_r<true, 64>(c);
+  return c.sh.d == 128 ? launch_score_r<false, 128>(c) : launch_score_r<false, 64>(c);
 }
 
 }  // namespace flowmm
