@@ -68,7 +68,10 @@ __device__ __forceinline__ unsigned long long same_slot_mask(bool member, int sl
 }
 
 // at most 64 registers: two workgroups of 16 waves then share a compute unit
-__global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw_shift) {
+// members_off: where (in ints from the start of the dynamic LDS) the member list is put together before it
+// goes to memory in whole lines, or -1 to write it directly (scattered 4-byte stores: every one of them
+// costs a 32-byte memory transaction)
+__global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw_shift, int members_off) {
   // [NW][B] per-wave counts, later write cursors; the slot runs fastest, so that the slots of a wave's 64
   // tokens and the 1024 slots of a scan step fall on different banks
   extern __shared__ int lds_tbl[];
@@ -176,6 +179,7 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
   __syncthreads();
 
   // pass 2: write the members, ascending inside every slot
+  int *members_dst = members_off >= 0 ? lds_tbl + members_off : members;
   if (wave < NW) {
     for (int i0 = r0; i0 < r1; i0 += 64 * kCsrAhead) {
       int slotv[kCsrAhead], keptv[kCsrAhead];
@@ -195,11 +199,15 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
         const unsigned long long below = m & ((1ull << lane) - 1);
         if (member) {
           const int cur = lds_tbl[wave * s.B + slot];
-          members[cur + __popcll(below)] = i;
+          members_dst[cur + __popcll(below)] = i;
           if (below == 0) lds_tbl[wave * s.B + slot] = cur + __popcll(m);
         }
       }
     }
+  }
+  if (members_off >= 0) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < seg_carry; i += kCsrThreads) members[i] = members_dst[i];
   }
 }
 
@@ -495,7 +503,15 @@ hipError_t launch_merge_w(const Ctx &c, int nw_shift, size_t lds) {
   if (e != hipSuccess) return e;
   {
     ProfScope ps(c.stream, KID_MERGE_CSR);
-    merge_csr_kernel<<<dim3(sh.batch, sh.Hkv, sh.n_layers), kCsrThreads, lds, c.stream>>>(c, nw_shift);
+    // the member list is put together in LDS when that leaves the compute units as many workgroups as before:
+    // two each, or one each when there are no more workgroups than compute units
+    const size_t with_members = lds + (size_t)sh.maxE * 4;
+    const long long wgs = (long long)sh.batch * sh.Hkv * sh.n_layers;
+    // (short lists are not worth the extra pass over them: 19 against 23 us at 3700 members per list)
+    const bool stage = sh.maxE >= 8192 &&
+                       (with_members <= kLdsBytes / 2 - 1024 || (wgs <= 256 && with_members <= kLdsBytes - 8 * 1024));
+    merge_csr_kernel<<<dim3(sh.batch, sh.Hkv, sh.n_layers), kCsrThreads, stage ? with_members : lds, c.stream>>>(
+        c, nw_shift, stage ? (int)(lds / 4) : -1);
   }
   {
     ProfScope ps(c.stream, KID_MERGE_TASKS);
