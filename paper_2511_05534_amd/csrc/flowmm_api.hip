@@ -228,8 +228,10 @@ flowmm_status build_layout(const flowmm_params *p, Layout &lo) {
     rg.pl_w = off; off += align256((size_t)units * 2 * sh.SBP * 4);
     rg.pl_n = off; off += align256((size_t)units * batch * 2 * 4);
     rg.pack = off; off += align256((size_t)units * 2 * sh.SBP * (sh.d * es + 16));
+    rg.ev_list = off; off += align256((size_t)units * T * 4);
+    rg.ev_n = off; off += align256((size_t)units * batch * 2 * 4);
   } else {
-    rg.pl_slot = rg.pl_tok = rg.pl_w = rg.pl_n = rg.pack = off;
+    rg.pl_slot = rg.pl_tok = rg.pl_w = rg.pl_n = rg.pack = rg.ev_list = rg.ev_n = off;
   }
   rg.plan_end = off;
   off = shared0;
@@ -290,6 +292,8 @@ void fill_ctx(Ctx &c, const Layout &lo, const flowmm_plan_buffers *plan, void *w
   c.pl_w = reinterpret_cast<float *>(ws + lo.rg.pl_w);
   c.pl_n = reinterpret_cast<int *>(ws + lo.rg.pl_n);
   c.pack = reinterpret_cast<uint4 *>(ws + lo.rg.pack);
+  c.ev_list = reinterpret_cast<int *>(ws + lo.rg.ev_list);
+  c.ev_n = reinterpret_cast<int *>(ws + lo.rg.ev_n);
   c.seg_off = reinterpret_cast<int *>(ws + lo.rg.seg_off);
   c.members = reinterpret_cast<int *>(ws + lo.rg.members);
   c.tasks = reinterpret_cast<int4 *>(ws + lo.rg.tasks);

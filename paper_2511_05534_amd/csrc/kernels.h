@@ -52,6 +52,8 @@ struct Ctx {
   float2 *part_stats;  // [Lyr][Hkv][tiles_score][R_pad]  (max, sum exp2) of each row over a tile
   float *rowstat;      // [Lyr][Hkv][batch][R_pad]        max + log2(sum exp2) of each row, +inf for padding rows
   float *cross_part;   // [Lyr][Hq][tiles_score]          cross-modal mass of a head over a tile
+  int *ev_list;        // [Lyr][Hkv][T]                   the tokens to be matched, per sequence in class order (text, then image)
+  int *ev_n;           // [Lyr][Hkv][batch][2]            how many of either class (all in the first one in a cross-modal layer)
   int *pl_slot;        // [Lyr][Hkv][2*SBP]               eligible pivots per (sequence, token class): their slots, ascending
   int *pl_tok;         // [Lyr][Hkv][2*SBP]               their positions
   float *pl_w;         // [Lyr][Hkv][2*SBP]               1/norm of those pivots (0 for a zero row)

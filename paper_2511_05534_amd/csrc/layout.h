@@ -95,7 +95,7 @@ struct Regions {
   size_t part_stats, rowstat, cross_part;                   // plan: score
   size_t decode_part;                                       // decode attention: [Lyr][Hq][batch][kDecodeMaxSplits][d+2]
   size_t flow_part;                                         // exact flow ratio: [Lyr][Hq][flowq_total]
-  size_t pl_slot, pl_tok, pl_w, pl_n, pack;                 // plan: match
+  size_t pl_slot, pl_tok, pl_w, pl_n, pack, ev_list, ev_n;  // plan: match
   size_t seg_off, members, tasks, n_tasks, multi, n_multi, partials, partial_w;  // merge
   size_t plan_end, merge_end;
 };

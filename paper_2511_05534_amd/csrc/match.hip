@@ -74,14 +74,14 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
   int tile = x - cu[b];
   const SeqInfo s = load_seq(meta, b);
   const bool cross = c.mode[l * sh.batch + b] != 0;
-  // token class of this tile: everything in a cross-modal layer, else text tiles then image tiles
-  int cls = 0, cbeg = 0, cn = s.L;
+  // The tiles walk over the select kernel's list of the tokens to be matched (no pivot among them).
+  // Token class of this tile: everything in a cross-modal layer, else text tiles then image tiles.
+  const int *ev_n = c.ev_n + (unit * sh.batch + b) * 2;
+  int cls = 0, cbeg = 0, cn = ev_n[0];
   if (!cross) {
-    const int t0 = (s.n_text + TILE - 1) / TILE;
-    if (tile < t0) {
-      cn = s.n_text;
-    } else {
-      tile -= t0; cls = 1; cbeg = s.n_text; cn = s.L - s.n_text;
+    const int t0 = (cn + TILE - 1) / TILE;
+    if (tile >= t0) {
+      tile -= t0; cls = 1; cbeg = cn; cn = ev_n[1];
     }
   }
   const int v0 = tile * TILE;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, half = lane >> 5;
   const uint4 *K = reinterpret_cast<const uint4 *>(c.K) + (long long)l * sh.ks_layer +
                    (long long)gkv * sh.ks_head + (long long)s.tok_off * sh.ks_tok;
-  const int *order = c.cls_order + s.tok_off + cbeg;
+  const int *ev = c.ev_list + unit * sh.T + s.tok_off + cbeg;
   int *assign = c.assign + unit * sh.T + s.tok_off;
   const int Bp = (s.B + 31) & ~31;
   const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b] + cls * Bp;
@@ -115,18 +115,10 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
   const bool active = wv0 < cn;
   uint4 kf[KS][NF];
   float shift[KS];
-  auto token_of = [&](int sub) {  // position of this lane's token of group sub (the class's last one past the end)
-    const int vc = min(wv0 + sub * 32 + n, cn - 1);
-    return cross ? vc : order[vc];
-  };
-  // Whether a token still waits for a pivot is asked for now, next to the key loads, and kept in
-  // LDS: the end of the kernel then has one dependent load (the slot of the winning list entry) left.
-  int tok[KS], state[KS];
+  // position of this lane's token of every group (the class's last one past the end)
+  int tok[KS];
 #pragma unroll
-  for (int sub = 0; sub < KS; ++sub) {
-    tok[sub] = token_of(sub);
-    state[sub] = assign[tok[sub]];
-  }
+  for (int sub = 0; sub < KS; ++sub) tok[sub] = ev[min(wv0 + sub * 32 + n, cn - 1)];
   // Their rows come in whole through the LDS that the pivot tiles use afterwards (every wave has its own
   // share of it), one token group at a time; rows that do not lie within 4 GiB, and rows too wide for that
   // share, are fetched fragment by fragment.
@@ -148,7 +140,7 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
 #pragma unroll
   for (int sub = 0; sub < KS; ++sub)
     if (half == 0)
-      lds_tok[wave * 32 * KS + sub * 32 + n] = (wv0 + sub * 32 + n < cn && state[sub] == -2) ? tok[sub] : -1;
+      lds_tok[wave * 32 * KS + sub * 32 + n] = wv0 + sub * 32 + n < cn ? tok[sub] : -1;
 #pragma unroll
   for (int sub = 0; sub < KS; ++sub) {
     float ss = 0.f;

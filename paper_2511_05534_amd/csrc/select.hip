@@ -104,6 +104,70 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   __syncthreads();  // kept[] is read back below; sh_rho is set
   const bool cross = (sh_rho > sh.theta) != (sh.invert_flow != 0);
 
+  // ---- the tokens to be matched, in class order --------------------------------------------------
+  // (all of them ascending in a cross-modal layer; the text tokens, then the image tokens in an
+  // intra-modal one).  The match kernel walks over this list, so pivots take no part in its contraction.
+  // Consecutive threads look at consecutive list positions (the flags come out of LDS without bank
+  // conflicts and the list goes to memory in nearly whole lines); the rank of a token is the count of
+  // the (round, wave) cells before its own plus the flagged lanes below it.
+  {
+    constexpr int KPT = 16, kWaves = kThreads / 64;
+    static_assert(KPT * kWaves <= 256, "one counter per (round, wave) in the histogram scratch");
+    int *ev = c.ev_list + unit * sh.T + s.tok_off;
+    const int *order = c.cls_order + s.tok_off;
+    const int *asg = staged ? reinterpret_cast<const int *>(lds_keys) : assign;
+    const int bound = cross ? s.L : s.n_text;  // class-order indices below it belong to the first class
+    int *cell = scratch.hist;                  // [KPT][kWaves] counts, then exclusive offsets
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    auto flagged = [&](int v, int &tok) {
+      tok = 0;
+      if (v >= s.L) return false;
+      tok = cross ? v : order[v];
+      return asg[tok] == -2;
+    };
+    int carry = 0, carry0 = 0;
+    for (int base = 0; base < s.L; base += KPT * kThreads) {
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const int v = base + j * kThreads + threadIdx.x;
+        int tok;
+        const bool f = flagged(v, tok);
+        const unsigned long long bal = __ballot(f), bal0 = __ballot(f && v < bound);
+        if (lane == 0) cell[j * kWaves + wave] = __popcll(bal) | (__popcll(bal0) << 16);
+      }
+      __syncthreads();
+      if (wave == 0) {  // exclusive scan of the KPT * kWaves cells in list order: four cells per lane
+        int v4[4], sum = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v4[k] = 4 * lane + k < KPT * kWaves ? cell[4 * lane + k] : 0; sum += v4[k]; }
+        int before = wave_inclusive_scan(sum) - sum;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (4 * lane + k < KPT * kWaves) cell[4 * lane + k] = before;
+          before += v4[k];
+        }
+        if (lane == 63) scratch.remaining = before;  // the total of this round
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const int v = base + j * kThreads + threadIdx.x;
+        int tok;
+        const bool f = flagged(v, tok);
+        const unsigned long long bal = __ballot(f);
+        if (f) ev[carry + (cell[j * kWaves + wave] & 0xffff) + __popcll(bal & ((1ull << lane) - 1))] = tok;
+      }
+      const int total = scratch.remaining;
+      carry += total & 0xffff;
+      carry0 += total >> 16;
+      __syncthreads();  // the cells are counted into again
+    }
+    if (threadIdx.x == 0) {
+      c.ev_n[(unit * sh.batch + b) * 2] = carry0;
+      c.ev_n[(unit * sh.batch + b) * 2 + 1] = carry - carry0;
+    }
+  }
+
   // ---- lists of eligible pivots per token class --------------------------------------------------
   const int Bp = (s.B + 31) & ~31;
   const long long lbase = unit * 2 * sh.SBP + 2 * (meta + meta[MW_OFF_CU_BP])[b];
