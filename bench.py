@@ -25,6 +25,8 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # Kernels that together make up one step of the method and share its algorithmic bytes: the two
 # streaming passes of the score (the row statistics of the softmax, then the column sums) need K once
 # between them by the method's own dependencies, so the group is credited one K read and is timed as a whole.
+# 1024 SIMDs x 2.4 GHz x 64 lanes / 18 issue cycles per softmax logit
+ALU_PEAK_LOGITS = 1024 * 2.4e9 * 64 / 18
 GROUPS = {"score_stats": "score", "score_combine": "score", "score_colsum": "score"}
 
 
@@ -339,6 +341,13 @@ def main():
         elif byt.get(name):
             steps_roofline[name] = {"bound": "hbm", "us": us, "GBs": byt[name] / (us * 1e-6) / 1e9,
                                     "frac": byt[name] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+            if name == "score":
+                # the same step against the vector units: both heavy passes turn every logit into a
+                # probability (fma, v_exp_f32 at a quarter of the rate, add, half a max3: 18 issue cycles per
+                # 64 logits and SIMD), flops["score"] / (2 d) logits per pass
+                logits = 2 * flops["score"] / (2.0 * wl.head_dim)
+                steps_roofline[name]["alu"] = {"logits": logits, "peak_logits_per_s": ALU_PEAK_LOGITS,
+                                               "frac": logits / (us * 1e-6) / ALU_PEAK_LOGITS}
     out = {
         "metric": "KV tokens merged/sec per GPU + achieved HBM GB/s (% of peak), full prefill cache",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
