@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kThreads, 4) void match_kernel(Ctx c) {
   // Their rows come in whole through the LDS that the pivot tiles use afterwards (every wave has its own
   // share of it), one token group at a time; rows that do not lie within 4 GiB, and rows too wide for that
   // share, are fetched fragment by fragment.
-  constexpr bool kStaged = 8 * 32 * NCH <= 2 * ROWS * RS;
+  constexpr bool kStaged = kMatchWaves * 32 * NCH <= 2 * ROWS * RS;
   if (kStaged && sh.rows32) {
 #pragma unroll
     for (int sub = 0; sub < KS; ++sub)
