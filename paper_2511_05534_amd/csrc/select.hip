@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   constexpr int NCH = Cfg<BF16, D>::NCH;
   __shared__ SelectScratch<kThreads> scratch;
   __shared__ SmallSelectScratch<kThreads> scratch_regs;
-  extern __shared__ unsigned lds_keys[];  // [min(maxL, kSelectRegisterKeys)] keys, then assignments
+  extern __shared__ __align__(16) unsigned lds_keys[];  // [min(maxL, kSelectRegisterKeys)] keys, then assignments
   __shared__ float lds_head[kThreads];
   __shared__ float sh_rho;
   const Shape &sh = c.sh;
@@ -83,15 +83,45 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(Ctx c) {
   // to memory in: keys come in and assignments go out through LDS, in coalesced rows.
   auto from_registers = [&](auto kpt_tag) {
     constexpr int KPT = decltype(kpt_tag)::value;
-    for (int i = threadIdx.x; i < s.L; i += kThreads) lds_keys[i] = imp[i];
-    __syncthreads();
     unsigned keys[KPT];
     const int i0 = threadIdx.x * KPT;
+    if ((reinterpret_cast<uintptr_t>(imp) & 15) == 0) {
+      // the thread's keys are KPT / 4 chunks of 16 bytes: all of them requested at once, no detour
 #pragma unroll
-    for (int j = 0; j < KPT; ++j) keys[j] = i0 + j < s.L ? lds_keys[i0 + j] : 0u;
+      for (int q = 0; q < KPT / 4; ++q) {
+        const int i = i0 + 4 * q;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (i + 3 < s.L) {
+          v = *reinterpret_cast<const uint4 *>(imp + i);
+        } else {
+          if (i < s.L) v.x = imp[i];
+          if (i + 1 < s.L) v.y = imp[i + 1];
+          if (i + 2 < s.L) v.z = imp[i + 2];
+        }
+        keys[4 * q] = v.x; keys[4 * q + 1] = v.y; keys[4 * q + 2] = v.z; keys[4 * q + 3] = v.w;
+      }
+    } else {
+      // a sequence that does not start on a 16-byte boundary: coalesced rows through LDS, KPT requests in flight
+      for (int base = 0; base < s.L; base += KPT * kThreads) {
+        unsigned v[KPT];
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+          const int i = base + j * kThreads + threadIdx.x;
+          v[j] = i < s.L ? imp[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+          const int i = base + j * kThreads + threadIdx.x;
+          if (i < s.L) lds_keys[i] = v[j];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) keys[j] = i0 + j < s.L ? lds_keys[i0 + j] : 0u;
+    }
     // the same LDS words take the assignments (the call starts with a barrier of its own)
     int *lds_assign = reinterpret_cast<int *>(lds_keys);
-    select_top_b_regs<kThreads, KPT>(keys, s.L, sh.W, s.B, kept, lds_assign, scratch_regs);
+    select_top_b_regs<kThreads, KPT, true>(keys, s.L, sh.W, s.B, kept, lds_assign, scratch_regs);
     __syncthreads();
     for (int i = threadIdx.x; i < s.L; i += kThreads) assign[i] = lds_assign[i];
   };

@@ -204,7 +204,10 @@ struct SmallSelectScratch {
 // wave on its own instead of being shared), and the compaction is one block scan.
 // keys: the thread's keys KPT t .. KPT t + KPT - 1 (anything where the index is >= L).  kept and
 // assign may be LDS or global.  Same results as select_top_b.
-template <int THREADS, int KPT>
+// VEC_ASSIGN: assign + KPT t is 16-byte aligned for every thread t; a thread's assignments then go out
+// as 16-byte chunks (consecutive words of LDS written one by one from 64 lanes KPT words apart meet
+// in a few banks).
+template <int THREADS, int KPT, bool VEC_ASSIGN = false>
 __device__ __forceinline__ void select_top_b_regs(const unsigned (&keys)[KPT], int L, int W, int B, int *kept,
                                                   int *assign, SmallSelectScratch<THREADS> &sc) {
   static_assert(KPT * THREADS <= 65535, "the packed scan keeps two 16-bit counts");
@@ -308,18 +311,35 @@ __device__ __forceinline__ void select_top_b_regs(const unsigned (&keys)[KPT], i
   int before = inc - packed;
   for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += sc.wave_sums[w];
   int gt_before = before & 0xffff, eq_before = before >> 16;
+  int mine[KPT];
 #pragma unroll
   for (int j = 0; j < KPT; ++j) {
     const int i = i0 + j;
     const bool gt = (gtm >> j) & 1u, eq = (eqm >> j) & 1u;
+    mine[j] = -2;
     if (i < L) {
       const bool is_kept = gt || (eq && eq_before < need_eq);
       const int slot = gt_before + min(eq_before, need_eq);
       if (is_kept) kept[slot] = i;
-      assign[i] = is_kept ? slot : -2;
+      mine[j] = is_kept ? slot : -2;
+      if (!VEC_ASSIGN) assign[i] = mine[j];
     }
     gt_before += gt;
     eq_before += eq;
+  }
+  if constexpr (VEC_ASSIGN) {
+    static_assert(KPT % 4 == 0, "whole 16-byte chunks");
+#pragma unroll
+    for (int q = 0; q < KPT / 4; ++q) {
+      const int i = i0 + 4 * q;
+      if (i + 3 < L) {
+        *reinterpret_cast<int4 *>(assign + i) = make_int4(mine[4 * q], mine[4 * q + 1], mine[4 * q + 2], mine[4 * q + 3]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (i + j < L) assign[i + j] = mine[4 * q + j];
+      }
+    }
   }
 }
 
