@@ -24,6 +24,11 @@ namespace {
 
 constexpr int kCsrThreads = kCsrWaves * 64;
 constexpr int kCsrAhead = 4;   // rounds of 64 tokens a walking wave loads ahead
+// Words of LDS in front of the counting table for the pivot positions of the longest budget (a whole number
+// of 16-byte chunks), or 0 when table and positions together would not fit: the positions then stay in memory.
+__host__ __device__ constexpr int csr_kept_words(int max_budget, int nw_shift) {
+  return ((size_t)max_budget << nw_shift) * 4 + (size_t)max_budget * 4 <= 144u * 1024u ? (max_budget + 3) & ~3 : 0;
+}
 constexpr int kSmallTask = 4;  // a slot with fewer members is merged by one row group (pivot + members = loads in flight)
 
 // Exclusive scan over the workgroup of a 64-bit value that packs several small counters (their
@@ -56,15 +61,20 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan_packed(unsign
   return lds_wave[wave] + inc - v;
 }
 
-// lanes of the wave that hold the same slot as this lane (only meaningful where member)
-__device__ __forceinline__ unsigned long long same_slot_mask(bool member, int slot, int nbits) {
-  unsigned long long m = __ballot(member);
+// How many lower lanes of the wave hold the same slot as this lane, and how many lanes do in all (only
+// meaningful where member).  One ballot per slot bit; the lanes that agree with this one on the bit
+// are ballot XNOR (bit ? ~0 : 0), taken on the two halves of the wave mask.
+__device__ __forceinline__ void same_slot_rank(bool member, int slot, int nbits, int &below, int &total) {
+  const unsigned long long mm = __ballot(member);
+  unsigned lo = (unsigned)mm, hi = (unsigned)(mm >> 32);
   for (int bit = 0; bit < nbits; ++bit) {
-    const bool one = (slot >> bit) & 1;
-    const unsigned long long bb = __ballot(member && one);
-    m &= one ? bb : ~bb;
+    const unsigned e = 0u - ((unsigned)(slot >> bit) & 1u);  // all ones where the bit is set
+    const unsigned long long bb = __ballot(member && e != 0u);
+    lo &= ~((unsigned)bb ^ e);
+    hi &= ~((unsigned)(bb >> 32) ^ e);
   }
-  return m;
+  below = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+  total = __popc(lo) + __popc(hi);
 }
 
 // at most 64 registers: two workgroups of 16 waves then share a compute unit
@@ -74,7 +84,9 @@ __device__ __forceinline__ unsigned long long same_slot_mask(bool member, int sl
 __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw_shift, int members_off) {
   // [NW][B] per-wave counts, later write cursors; the slot runs fastest, so that the slots of a wave's 64
   // tokens and the 1024 slots of a scan step fall on different banks
-  extern __shared__ int lds_tbl[];
+  // in front of it the pivot positions of the sequence (the test "is this token its slot's pivot" then
+  // needs no second trip to memory behind the token's assignment)
+  extern __shared__ int lds_csr[];
   __shared__ unsigned long long lds_wave[kCsrWaves + 1];
   const Shape &sh = c.sh;
   const int *meta = c.meta;
@@ -99,6 +111,11 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
   const int range = ((s.L + NW - 1) / NW + 63) & ~63;  // tokens per walking wave
   const int r0 = wave * range, r1 = min(s.L, r0 + range);
 
+  const int kept_words = csr_kept_words(sh.maxB, nw_shift);
+  int *lds_tbl = lds_csr + kept_words;
+  const int *kept_near = kept_words ? lds_csr : kept;  // where the walks below look the pivot of a slot up
+  if (kept_words)
+    for (int i = threadIdx.x; i < s.B; i += kCsrThreads) lds_csr[i] = kept[i];
   for (int i = threadIdx.x; i < s.B * NW; i += kCsrThreads) lds_tbl[i] = 0;
   __syncthreads();
 
@@ -113,14 +130,13 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
         slotv[u] = i < r1 ? assign[i] : -1;
       }
 #pragma unroll
-      for (int u = 0; u < kCsrAhead; ++u) keptv[u] = slotv[u] >= 0 ? kept[slotv[u]] : -1;
+      for (int u = 0; u < kCsrAhead; ++u) keptv[u] = slotv[u] >= 0 ? kept_near[slotv[u]] : -1;
 #pragma unroll
       for (int u = 0; u < kCsrAhead; ++u) {
         if (i0 + 64 * u >= r1) break;
         const int i = i0 + 64 * u + lane, slot = slotv[u];
-        const bool member = slot >= 0 && keptv[u] != i;
-        const unsigned long long m = same_slot_mask(member, slot, nbits);
-        if (member && (m & ((1ull << lane) - 1)) == 0) lds_tbl[wave * s.B + slot] += __popcll(m);
+        // counting needs no order: the few lanes of a round that share a slot take their turns in the LDS
+        if (slot >= 0 && keptv[u] != i) atomicAdd(&lds_tbl[wave * s.B + slot], 1);
       }
     }
   }
@@ -179,7 +195,7 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
   __syncthreads();
 
   // pass 2: write the members, ascending inside every slot
-  int *members_dst = members_off >= 0 ? lds_tbl + members_off : members;
+  int *members_dst = members_off >= 0 ? lds_csr + members_off : members;
   if (wave < NW) {
     for (int i0 = r0; i0 < r1; i0 += 64 * kCsrAhead) {
       int slotv[kCsrAhead], keptv[kCsrAhead];
@@ -189,18 +205,18 @@ __global__ __launch_bounds__(kCsrThreads, 8) void merge_csr_kernel(Ctx c, int nw
         slotv[u] = i < r1 ? assign[i] : -1;
       }
 #pragma unroll
-      for (int u = 0; u < kCsrAhead; ++u) keptv[u] = slotv[u] >= 0 ? kept[slotv[u]] : -1;
+      for (int u = 0; u < kCsrAhead; ++u) keptv[u] = slotv[u] >= 0 ? kept_near[slotv[u]] : -1;
 #pragma unroll
       for (int u = 0; u < kCsrAhead; ++u) {
         if (i0 + 64 * u >= r1) break;
         const int i = i0 + 64 * u + lane, slot = slotv[u];
         const bool member = slot >= 0 && keptv[u] != i;
-        const unsigned long long m = same_slot_mask(member, slot, nbits);
-        const unsigned long long below = m & ((1ull << lane) - 1);
+        int below, total;
+        same_slot_rank(member, slot, nbits, below, total);
         if (member) {
           const int cur = lds_tbl[wave * s.B + slot];
-          members_dst[cur + __popcll(below)] = i;
-          if (below == 0) lds_tbl[wave * s.B + slot] = cur + __popcll(m);
+          members_dst[cur + below] = i;
+          if (below == 0) lds_tbl[wave * s.B + slot] = cur + total;
         }
       }
     }
@@ -539,7 +555,8 @@ static int merge_csr_wave_shift(int max_budget) {
 }
 
 size_t merge_csr_lds_bytes(int max_budget) {
-  return (size_t)max_budget * (1u << merge_csr_wave_shift(max_budget)) * 4;
+  const int shift = merge_csr_wave_shift(max_budget);
+  return (((size_t)max_budget << shift) + csr_kept_words(max_budget, shift)) * 4;
 }
 
 hipError_t launch_merge(const Ctx &c) {

@@ -55,6 +55,9 @@ SMALL_CASES = {
     "select_8_keys_per_thread": dict(Hq=2, Hkv=1, d=64, W=16, n_layers=1, pct=(6,), spans=((300, 5000, 700),)),
     "select_16_keys_per_thread": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, pct=(4,), spans=((400, 9000, 1100),)),
     "select_keys_from_memory": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, pct=(3,), spans=((500, 15000, 1000),)),
+    # a budget whose pivot positions do not fit in LDS next to the member-counting table of the merge (one
+    # wave then walks the tokens and looks the pivots up in memory)
+    "budget_of_19000": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, budgets=(19000,), spans=((500, 19000, 800),)),
     "select_long_and_short_in_a_batch": dict(Hq=1, Hkv=1, d=64, W=16, n_layers=1, pct=(3, 10),
                                              spans=((500, 15000, 1000), (40, 300, 60))),
 }
