@@ -67,3 +67,35 @@ def test_static_scratch_refuses_shapes_beyond_the_array():
         fb.flowmm_plan_merge_static(params, t.data_ptr(), t.data_ptr() + (1 << 40), t.data_ptr(), [t.data_ptr()] * 6,
                                     t.data_ptr() + (1 << 41), t.data_ptr() + (1 << 42))
     assert ei.value.status == fb.FLOWMM_EWORKSPACE and "scratch" in ei.value.message
+
+
+def test_static_entry_point_in_a_hip_graph():
+    """What the entry point is for: a caller under stream capture.  Every replay of the captured call (with
+    eager work and a synchronisation in between) must reproduce the eager result of flowmm_plan_merge."""
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    for name, flags in (("no_alloc_graph_unit", 0), ("no_alloc_graph_generic", 1)):
+        w = wl.make_workload(name, "bf16", 33, 3, 4, 2, 128, 32, [[37, 411, 83]], [10])
+        K, V, Q = fb.upload_workload(w, "cuda:0")
+        params = fb.Params.from_workload(w, flags=flags)
+        ref = fb.DeviceBuffers(params)
+        ref.plan_merge(K, V, Q, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        got = fb.DeviceBuffers(params)
+        got.workspace = None
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            got.plan_merge_static(K, V, Q, side.cuda_stream)  # first use outside the capture: symbol look-up, function attributes
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            got.plan_merge_static(K, V, Q, torch.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            for n in fb.PLAN_FIELDS + ("K_out", "V_out"):
+                getattr(got, n).fill_(0)
+            torch.randn(1 << 20, device="cuda:0").sum().item()  # unrelated eager work and a synchronisation
+            graph.replay()
+            torch.cuda.synchronize()
+            _assert_identical(ref, got, (name, rep))
