@@ -193,6 +193,99 @@ def bench_decode(args, wl, dev):
     }))
 
 
+def bench_cache(args, wl, dev):
+    """Decode-time maintenance of the compacted cache: every sequence holds its budget of merged rows plus
+    a quarter of that as head room; a cycle appends one token per step until the head room is full and then
+    compresses every sequence back to its budget (append equation of the Preliminary section; the re-merge
+    is this build's reading of how the method is kept up while decoding)."""
+    import numpy as np
+    import torch
+    from paper_2511_05534_amd import binding as fb
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    s = 2 if wl.dtype == "bf16" else 4
+    Lyr, Hq, Hkv, d, W, batch = wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.batch
+    Bs = list(wl.budgets)
+    R = max(1, min(Bs) // 4)
+    cu_cap = np.concatenate([[0], np.cumsum([B + R for B in Bs])]).astype(np.int32)
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    Kc = torch.randn((Lyr, Hkv, int(cu_cap[-1]), d), generator=gen, device=dev).to(tdt)
+    Vc = torch.randn((Lyr, Hkv, int(cu_cap[-1]), d), generator=gen, device=dev).to(tdt)
+    k_new = torch.randn((Lyr, Hkv, batch, d), generator=gen, device=dev).to(tdt)
+    v_new = torch.randn((Lyr, Hkv, batch, d), generator=gen, device=dev).to(tdt)
+    Qw = torch.randn((Lyr, Hq, W, d), generator=gen, device=dev).to(tdt)
+    cache = fb.Params(Lyr, Hq, Hkv, d, wl.dtype, [B + R for B in Bs], Bs, [[(0, B + R, 0)] for B in Bs], W, 0.0,
+                      [4.0 / B for B in Bs], q_strides=(Hq * W * d, W * d, d))
+    plans, ws_bytes = [], 0
+    for b in range(batch):
+        n, B = Bs[b] + R, Bs[b]
+        sizes, ws = fb.flowmm_cache_remerge_sizes(cache, cu_cap, b, n)
+        ws_bytes = max(ws_bytes, ws)
+        plans.append([torch.empty(sz, dtype=torch.uint8, device=dev) for sz in sizes])
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    lengths = list(Bs)
+
+    def appends():
+        for _ in range(R):
+            fb.flowmm_cache_append(cache, cu_cap, lengths, Kc.data_ptr(), Vc.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), stream)
+            for b in range(batch):
+                lengths[b] += 1
+
+    def remerges():
+        for b in range(batch):
+            fb.flowmm_cache_remerge(cache, cu_cap, lengths, b, Kc.data_ptr(), Vc.data_ptr(), Qw.data_ptr(),
+                                    [t.data_ptr() for t in plans[b]], workspace.data_ptr(), ws_bytes, stream)
+            lengths[b] = Bs[b]
+
+    cycles = max(1, args.steps // 10)
+    for _ in range(max(1, args.warmup // 10)):
+        appends(); remerges()
+    torch.cuda.synchronize()
+    # one more cycle with every kernel bracketed by events: what the GPU spends, apart from the host's enqueueing
+    fb.flowmm_profile_select("all")
+    appends(); remerges()
+    torch.cuda.synchronize()
+    prof = fb.flowmm_profile_collect()
+    fb.flowmm_profile_select("")
+    k_append = 1e3 * prof["cache_append"][0] / max(prof["cache_append"][1], 1)
+    k_remerge = {k: 1e3 * ms for k, (ms, n) in prof.items() if n and k != "cache_append"}
+    t_app = t_rem = 0.0
+    for _ in range(cycles):
+        t0 = time.perf_counter()
+        appends()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        remerges()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        t_app += t1 - t0
+        t_rem += t2 - t1
+    us_append = 1e6 * t_app / (cycles * R)
+    us_remerge = 1e6 * t_rem / cycles
+    units = Lyr * Hkv
+    row = d * s
+    G = Hq // Hkv
+    rem_bytes = sum(units * (3 * (B + R) * row + 2 * B * row + G * W * row + 12 * (B + R)) for B in Bs)
+    app_bytes = units * batch * 2 * 2 * row  # the new K and V rows read and written
+    per_token = us_append + us_remerge / R
+    print(json.dumps({
+        "metric": "decode-time maintenance of the compacted cache, microseconds per generated token (appends + re-merge amortised)",
+        "value": per_token, "unit": "us/token", "n_gpus": 1, "steps": cycles, "warmup": max(1, args.warmup // 10),
+        "ms_per_step": (us_append * R + us_remerge) / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {wl.name}", "layers": Lyr, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
+                   "budgets": Bs, "head_room": R, "window": W, "entry_point": "flowmm_cache_append + flowmm_cache_remerge",
+                   "step": "one cycle: head_room appends, then every sequence back to its budget"},
+        "roofline": {"bound": "hbm", "kernel": "re-merge of all sequences (the kernels of flowmm_plan_merge on the cache rows)",
+                     "achieved": rem_bytes / (us_remerge * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": rem_bytes / (us_remerge * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": rem_bytes},
+        "append": {"us_per_step": us_append, "kernel_us": k_append, "bytes": app_bytes,
+                   "note": "a step is one call through the Python binding: its time is the host's, the kernel's is kernel_us"},
+        "remerge": {"us_per_cycle": us_remerge, "bytes": rem_bytes, "kernels_us_per_cycle": k_remerge},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,6 +304,8 @@ def main():
                     help="time flowmm_flow_exact (the interaction ratio over all prompt queries) instead of the merge path")
     ap.add_argument("--decode", action="store_true",
                     help="time flowmm_decode_attention over compacted caches of this configuration at 100/50/35/20/5 %% budget")
+    ap.add_argument("--cache", action="store_true",
+                    help="time flowmm_cache_append / flowmm_cache_remerge cycles on compacted caches of this configuration")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg; 0 skips it")
     ap.add_argument("--kernel", type=str, default="", help="kernel to report the roofline for (default: the slowest)")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -236,6 +331,8 @@ def main():
         return bench_flow_exact(args, wl, dev)
     if args.decode:
         return bench_decode(args, wl, dev)
+    if args.cache:
+        return bench_cache(args, wl, dev)
     K, V, Q = fb.upload_workload(wl, dev)
     params = fb.Params.from_workload(wl)
     bufs = fb.DeviceBuffers(params, dev)
